@@ -1,0 +1,205 @@
+/*
+ * sere.h - C ABI of the MI355X (gfx950) batch-decode MoE layer with SERE,
+ * similarity-based expert re-routing.
+ *
+ * One call = one decode step of one MoE layer over a batch of T tokens:
+ * router top-K, batch-wide primary-expert selection, re-routing of secondary
+ * experts onto their most similar primary expert (keeping critical experts),
+ * compaction of the token-to-expert map, and the grouped SwiGLU expert FFN
+ * over the surviving experts only.
+ *
+ * Conventions that hold for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, at least
+ *     16-byte aligned, dense row-major with the last index contiguous.
+ *     Inputs are never written.  The library allocates nothing per call and
+ *     writes only to `out`, to the non-NULL members of `sere_route_out` and
+ *     to `workspace`.
+ *   - `dtype` selects the storage of hidden states, router weights, expert
+ *     weights and the layer output: SERE_F32 (IEEE binary32) or SERE_BF16
+ *     (bfloat16).  The similarity matrix and gate weights are always fp32,
+ *     indices int32.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No call synchronises the device or copies to the
+ *     host; results are valid once the caller has synchronised the stream.
+ *   - Return value: SERE_OK (0) or a negative SERE_ERR_* code.  All argument
+ *     checks happen before anything is enqueued, so a failing call has no
+ *     device side effects.  No exception or abort crosses this boundary.
+ *   - Not checked on the device (preconditions): hidden states, router
+ *     weights and `sim` are finite; `topk_ids` handed to sere_reroute lie in
+ *     [0, M).
+ *   - Calls are re-entrant as long as concurrent calls use distinct
+ *     workspaces and outputs.
+ *   - Expert indices are 0-based.
+ */
+#ifndef SERE_H
+#define SERE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SERE_F32 0
+#define SERE_BF16 1
+
+#define SERE_OK 0
+#define SERE_ERR_NULL_PTR (-1)            /* a required pointer is NULL                  */
+#define SERE_ERR_BAD_SHAPE (-2)           /* a size is out of the supported range        */
+#define SERE_ERR_BAD_TOPK (-3)            /* K > M, or S outside [1, K]                  */
+#define SERE_ERR_BAD_DTYPE (-4)           /* dtype is neither SERE_F32 nor SERE_BF16     */
+#define SERE_ERR_MISALIGNED (-5)          /* a pointer is not 16-byte aligned            */
+#define SERE_ERR_WORKSPACE_TOO_SMALL (-6) /* workspace_bytes < sere_workspace_bytes()    */
+#define SERE_ERR_BAD_FLAGS (-7)           /* flags != 0                                  */
+#define SERE_ERR_NONFINITE_THRESHOLD (-8) /* threshold is NaN or infinite                */
+#define SERE_ERR_HIP (-9)                 /* a HIP launch reported an error              */
+
+#define SERE_MAX_EXPERTS 256
+#define SERE_MAX_SHARED 16
+#define SERE_MAX_TOKENS 65536
+
+/*
+ * Problem description.  Names follow the paper: T tokens in the decode batch,
+ * d_h hidden size, M routed experts, K experts per token, d_m expert
+ * intermediate size (appendix "Preliminaries on MoEs"); S = `select_top_k`,
+ * the number of top-ranked experts per token that form the primary set, and
+ * rho = `threshold`, the similarity below which a secondary expert is kept as
+ * a critical expert (Sec. 3.2.2; the two knobs of the appendix on
+ * hyper-parameters).
+ */
+typedef struct sere_config {
+  int32_t num_tokens;   /* T, 1 .. SERE_MAX_TOKENS                                   */
+  int32_t hidden;       /* d_h, positive multiple of 64                              */
+  int32_t num_experts;  /* M routed experts, 1 .. SERE_MAX_EXPERTS                   */
+  int32_t top_k;        /* K, 1 .. M                                                 */
+  int32_t inter;        /* d_m, positive multiple of 64                              */
+  int32_t num_shared;   /* always-on shared experts, 0 .. SERE_MAX_SHARED; they see
+                           every token with weight 1 and take no part in routing    */
+  int32_t dtype;        /* SERE_F32 | SERE_BF16                                      */
+  int32_t select_top_k; /* S, 1 .. K; S == K leaves the routing unchanged            */
+  float threshold;      /* rho, finite; rho <= 0 disables the critical-expert test
+                           (every secondary expert is re-routed), as in the paper's
+                           re-routing algorithm                                     */
+  int32_t flags;        /* reserved, must be 0                                       */
+} sere_config;
+
+/*
+ * Optional routing outputs; every member may be NULL (then that result stays
+ * internal).  A = T*K.  "Slot" k of token t is the k-th ranked expert of the
+ * router's ordered list R(t).
+ */
+typedef struct sere_route_out {
+  int32_t *topk_ids;       /* [T,K]  I : router's experts by descending logit; equal
+                                      logits: lower index first                      */
+  float *topk_weights;     /* [T,K]  W : softmax over the K selected logits           */
+  int32_t *rerouted_ids;   /* [T,K]  I': slots k < S unchanged; a slot keeps
+                                      duplicates if two slots of a token land on
+                                      the same expert                                */
+  int32_t *count_before;   /* [M]    slots per expert under I                         */
+  int32_t *count_after;    /* [M]    slots per expert under I'                        */
+  int32_t *primary_mask;   /* [M]    1 iff the expert is in the primary set           */
+  int32_t *num_active;     /* [2]    experts with a non-zero count {under I, under I'} */
+  int32_t *expert_offsets; /* [M+1]  exclusive prefix sum of count_after              */
+  int32_t *sorted_token;   /* [A]    token of each slot, grouped by expert (ascending
+                                      expert, then token, then slot)                 */
+  int32_t *sorted_slot;    /* [A]    slot index k of the same entries                 */
+} sere_route_out;
+
+/* Bytes of device workspace the calls below need for `cfg` (256-byte aligned
+ * base expected); 0 if `cfg` is NULL or invalid. */
+size_t sere_workspace_bytes(const sere_config *cfg);
+
+/*
+ * Routing half of the layer (Sec. 3.2.2 Steps 1-3 on top of the router):
+ * router logits <x_t, Wr_e>, ordered top-K and gate (appendix "Preliminaries
+ * on MoEs", top-k gating equation), primary set (primary-set equation), most
+ * similar primary expert and threshold test per secondary expert (arg-max and
+ * re-routing-condition equations; ties go to the lower index, scan order of
+ * the appendix re-routing algorithm), final active set and the re-grouped
+ * token-to-expert map (final-set equation).
+ *   hidden   [T, d_h]  dtype
+ *   router_w [M, d_h]  dtype, row e = router weights of expert e
+ *   sim      [M, M]    fp32, sim[u*M + v] = similarity of secondary expert u
+ *                      (row) to candidate primary expert v (column); the
+ *                      diagonal is never read; need not be symmetric
+ * Router logits are accumulated in fp64, so the ordering equals that of exact
+ * arithmetic except for logits closer than ~1e-12.
+ */
+int sere_route(const sere_config *cfg, const void *hidden, const void *router_w,
+               const float *sim, const sere_route_out *out, void *workspace,
+               size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The re-routing step alone, with the signature of the paper's appendix
+ * algorithm "CUDA-accelerated SERE": top-K indices in, re-routed indices out.
+ *   topk_ids [T, K] int32, already ordered by descending router weight.
+ * `out->topk_ids` and `out->topk_weights` are ignored; cfg->hidden, inter,
+ * num_shared and dtype are not used but must still be valid.
+ */
+int sere_reroute(const sere_config *cfg, const int32_t *topk_ids, const float *sim,
+                 const sere_route_out *out, void *workspace, size_t workspace_bytes,
+                 void *hip_stream);
+
+/*
+ * Full decode step with re-routing:
+ *   out[t] = sum_k W[t,k] * E_{I'[t,k]}(x_t) + sum_s Eshared_s(x_t)
+ * with E(x) = W_down (silu(W_gate x) * (W_up x))  (appendix "Preliminaries on
+ * MoEs", layer-output and expert equations).  The gate weights W are the
+ * router's and are not changed by re-routing (Sec. 3.2.2 Step 2).  Only the
+ * experts that still own a slot under I' (plus the shared experts) are read
+ * from memory, each exactly once.
+ *   w_gate_up      [M, 2*d_m, d_h]     dtype; rows 0..d_m-1 gate, d_m..2*d_m-1 up
+ *   w_down         [M, d_h, d_m]       dtype
+ *   shared_gate_up [n_sh, 2*d_m, d_h]  dtype, NULL iff num_shared == 0
+ *   shared_down    [n_sh, d_h, d_m]    dtype, NULL iff num_shared == 0
+ *   out            [T, d_h]            dtype; fp32 accumulation, one rounding
+ *   dbg            optional routing outputs (may be NULL)
+ * The intermediate silu(g)*u is kept at fp32 precision (for SERE_BF16 on the
+ * matrix cores: as a bf16 high part plus a bf16 low part).
+ */
+int sere_moe_decode(const sere_config *cfg, const void *hidden, const void *router_w,
+                    const void *w_gate_up, const void *w_down, const void *shared_gate_up,
+                    const void *shared_down, const float *sim, void *out,
+                    const sere_route_out *dbg, void *workspace, size_t workspace_bytes,
+                    void *hip_stream);
+
+/*
+ * The same step without re-routing: the standard top-K MoE layer (I' = I).
+ * cfg->select_top_k and cfg->threshold are validated but have no effect: the
+ * call behaves as select_top_k == top_k (so `primary_mask` marks every
+ * activated expert).
+ */
+int sere_moe_decode_baseline(const sere_config *cfg, const void *hidden, const void *router_w,
+                             const void *w_gate_up, const void *w_down,
+                             const void *shared_gate_up, const void *shared_down, void *out,
+                             const sere_route_out *dbg, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel the calls
+ * above enqueue is bracketed by HIP events on the caller's stream (at most
+ * SERE_TIMING_MAX_RECORDS launches are kept, later ones are not recorded).
+ * sere_stage_timing_read waits for the recorded events, adds the elapsed
+ * milliseconds and launch counts per stage into the two arrays of
+ * SERE_NUM_STAGES entries, and clears the records.  Process-global, not
+ * thread-safe, and slower than normal operation: never enable it while
+ * measuring whole-step latency.
+ */
+#define SERE_STAGE_ROUTER 0   /* router logits                           */
+#define SERE_STAGE_ROUTE 1    /* top-K, gate, re-route, compaction       */
+#define SERE_STAGE_GATE_UP 2  /* gate/up projections + SiLU * up         */
+#define SERE_STAGE_DOWN 3     /* down projection                         */
+#define SERE_STAGE_COMBINE 4  /* weighted sum over slots, output store   */
+#define SERE_NUM_STAGES 5
+#define SERE_TIMING_MAX_RECORDS 8192
+int sere_stage_timing(int enable);
+int sere_stage_timing_read(double *total_ms, int32_t *launches);
+
+/* Static, human-readable text for a status code. */
+const char *sere_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SERE_H */

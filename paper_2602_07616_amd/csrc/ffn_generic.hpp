@@ -1,0 +1,167 @@
+// Grouped expert FFN on the vector ALU (any dtype, any tokens-per-expert) and
+// the weighted combine.  Expert equations: appendix "Preliminaries on MoEs"
+// (E(x) = (silu(x W_gate) * (x W_up)) W_down, y = sum_i P_i E_i(x)).
+//
+// A "work item" is one surviving expert (or one shared expert) together with
+// the rows [off, off+cnt) of the expert-sorted slot list that it must serve.
+// The number of items is only known on the device, so every grid is sized for
+// the worst case and blocks beyond n_work leave at once.
+#pragma once
+
+#include "common.hpp"
+
+namespace sere {
+
+struct FfnArgs {
+  const void* hidden;          // [T, dh]
+  const void* w_gate_up;       // [M, 2*dm, dh]
+  const void* w_down;          // [M, dh, dm]
+  const void* shared_gate_up;  // [n_sh, 2*dm, dh]
+  const void* shared_down;     // [n_sh, dh, dm]
+  const int32_t* sorted_token; // [R] token of each sorted row (R = A + n_sh*T)
+  const int32_t* work_expert;
+  const int32_t* work_off;
+  const int32_t* work_cnt;
+  const int32_t* n_work;
+  float* h;                    // [R, dm] fp32: silu(gate) * up
+  float* y;                    // [ksplit, R, dh] fp32 partial down projections
+  int T, dh, dm, M, K, n_sh;
+  int ksplit;                  // slices of dm in the down projection
+  int rows;                    // R
+};
+
+template <int DT>
+__device__ __forceinline__ const void* expert_base(const void* routed, const void* shared, int e,
+                                                   int M, size_t per_expert_elems) {
+  const char* b = static_cast<const char*>(e < M ? routed : shared);
+  return b + static_cast<size_t>(e < M ? e : e - M) * per_expert_elems * Store<DT>::bytes;
+}
+
+constexpr int kGenTok = 8;   // tokens served per pass over a weight row
+constexpr int kGenJB = 16;   // intermediate indices per block (gate/up)
+constexpr int kGenRB = 16;   // output rows per block (down)
+
+// h[row, j] = silu(<Wg_j, x>) * <Wu_j, x>.  grid (ceil(dm/kGenJB), M + n_sh), 256 threads.
+template <int DT>
+__global__ __launch_bounds__(256) void ffn_gateup_generic(FfnArgs p) {
+  const int w = blockIdx.y;
+  if (w >= *p.n_work) return;
+  const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
+  const int dh = p.dh, dm = p.dm;
+  const void* W = expert_base<DT>(p.w_gate_up, p.shared_gate_up, e, p.M, static_cast<size_t>(2) * dm * dh);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int jj = wave; jj < kGenJB; jj += 4) {
+    const int j = blockIdx.x * kGenJB + jj;
+    if (j >= dm) break;
+    for (int tc = 0; tc < cnt; tc += kGenTok) {
+      const int nt = min(kGenTok, cnt - tc);
+      int tok[kGenTok];
+#pragma unroll
+      for (int q = 0; q < kGenTok; ++q) tok[q] = q < nt ? p.sorted_token[off + tc + q] : 0;
+      float ag[kGenTok], au[kGenTok];
+#pragma unroll
+      for (int q = 0; q < kGenTok; ++q) ag[q] = au[q] = 0.0f;
+      for (int i = lane * 8; i < dh; i += 512) {
+        float wg[8], wu[8];
+        load8<DT>(W, static_cast<size_t>(j) * dh + i, wg);
+        load8<DT>(W, static_cast<size_t>(dm + j) * dh + i, wu);
+#pragma unroll
+        for (int q = 0; q < kGenTok; ++q) {
+          if (q < nt) {
+            float xv[8];
+            load8<DT>(p.hidden, static_cast<size_t>(tok[q]) * dh + i, xv);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+              ag[q] = fmaf(wg[c], xv[c], ag[q]);
+              au[q] = fmaf(wu[c], xv[c], au[q]);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kGenTok; ++q) {
+        if (q < nt) {
+          const float g = wave_sum(ag[q]), u = wave_sum(au[q]);
+          if (lane == 0) p.h[static_cast<size_t>(off + tc + q) * dm + j] = silu(g) * u;
+        }
+      }
+    }
+  }
+}
+
+// y[row, r] = <Wd_r, h[row]>.  grid (ceil(dh/kGenRB), M + n_sh), 256 threads.
+template <int DT>
+__global__ __launch_bounds__(256) void ffn_down_generic(FfnArgs p) {
+  const int w = blockIdx.y;
+  if (w >= *p.n_work) return;
+  const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
+  const int dh = p.dh, dm = p.dm;
+  const void* W = expert_base<DT>(p.w_down, p.shared_down, e, p.M, static_cast<size_t>(dh) * dm);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int rr = wave; rr < kGenRB; rr += 4) {
+    const int r = blockIdx.x * kGenRB + rr;
+    if (r >= dh) break;
+    for (int tc = 0; tc < cnt; tc += kGenTok) {
+      const int nt = min(kGenTok, cnt - tc);
+      float acc[kGenTok];
+#pragma unroll
+      for (int q = 0; q < kGenTok; ++q) acc[q] = 0.0f;
+      for (int j = lane * 8; j < dm; j += 512) {
+        float wd[8];
+        load8<DT>(W, static_cast<size_t>(r) * dm + j, wd);
+#pragma unroll
+        for (int q = 0; q < kGenTok; ++q) {
+          if (q < nt) {
+            float hv[8];
+            load8<SERE_F32>(p.h, static_cast<size_t>(off + tc + q) * dm + j, hv);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[q] = fmaf(wd[c], hv[c], acc[q]);
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kGenTok; ++q) {
+        if (q < nt) {
+          const float v = wave_sum(acc[q]);
+          if (lane == 0) p.y[static_cast<size_t>(off + tc + q) * dh + r] = v;
+        }
+      }
+    }
+  }
+}
+
+struct CombineArgs {
+  const float* y;            // [ksplit, R, dh]
+  const float* topk_w;       // [T, K]
+  const int32_t* slot_pos;   // [T*K]
+  void* out;                 // [T, dh]
+  int T, dh, K, n_sh, ksplit, rows;
+};
+
+// out[t, r] = sum_k W[t,k] * y[pos(t,k), r] + sum_s y[A + s*T + t, r]; slots in
+// ascending k, then shared experts; fp32, one rounding to the output dtype.
+// grid (ceil(dh/256), T), 256 threads.
+template <int DT>
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs p) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  const int t = blockIdx.y;
+  if (r >= p.dh) return;
+  const size_t slice = static_cast<size_t>(p.rows) * p.dh;
+  float acc = 0.0f;
+  for (int k = 0; k < p.K; ++k) {
+    const int pos = p.slot_pos[t * p.K + k];
+    float v = 0.0f;
+    for (int s = 0; s < p.ksplit; ++s) v += p.y[s * slice + static_cast<size_t>(pos) * p.dh + r];
+    acc = fmaf(p.topk_w[t * p.K + k], v, acc);
+  }
+  const int A = p.T * p.K;
+  for (int sh = 0; sh < p.n_sh; ++sh) {
+    const int pos = A + sh * p.T + t;
+    float v = 0.0f;
+    for (int s = 0; s < p.ksplit; ++s) v += p.y[s * slice + static_cast<size_t>(pos) * p.dh + r];
+    acc += v;
+  }
+  store1<DT>(p.out, static_cast<size_t>(t) * p.dh + r, acc);
+}
+
+}  // namespace sere

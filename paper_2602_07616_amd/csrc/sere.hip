@@ -1,0 +1,428 @@
+// Host side of the C ABI declared in include/sere.h: argument validation,
+// workspace layout and kernel launches.  Nothing here synchronises the device.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "common.hpp"
+#include "ffn_generic.hpp"
+#include "route_kernels.hpp"
+
+namespace sere {
+
+// ---------------------------------------------------------------- layout ---
+struct Layout {
+  size_t logits, topk_ids, topk_w, rerouted, cnt_before, cnt_after, primary, num_active, offsets,
+      sorted_token, sorted_slot, slot_pos, work_expert, work_off, work_cnt, n_work, h, y, total;
+  int rows;    // A + n_sh*T rows of the sorted slot list
+  int ksplit;  // slices of d_m in the down projection
+};
+
+static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+static int down_ksplit(const sere_config& c) { return 1; }
+
+static Layout make_layout(const sere_config& c) {
+  Layout l{};
+  const size_t T = c.num_tokens, M = c.num_experts, K = c.top_k, A = T * K;
+  const size_t R = A + static_cast<size_t>(c.num_shared) * T;
+  const size_t W = M + c.num_shared;
+  l.rows = static_cast<int>(R);
+  l.ksplit = down_ksplit(c);
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + bytes);
+    return at;
+  };
+  l.logits = take(T * M * sizeof(double));
+  l.topk_ids = take(A * 4);
+  l.topk_w = take(A * 4);
+  l.rerouted = take(A * 4);
+  l.cnt_before = take(M * 4);
+  l.cnt_after = take(M * 4);
+  l.primary = take(M * 4);
+  l.num_active = take(2 * 4);
+  l.offsets = take((M + 1) * 4);
+  l.sorted_token = take(R * 4);
+  l.sorted_slot = take(A * 4);
+  l.slot_pos = take(A * 4);
+  l.work_expert = take(W * 4);
+  l.work_off = take(W * 4);
+  l.work_cnt = take(W * 4);
+  l.n_work = take(4);
+  l.h = take(R * c.inter * sizeof(float));
+  l.y = take(static_cast<size_t>(l.ksplit) * R * c.hidden * sizeof(float));
+  l.total = o;
+  return l;
+}
+
+// ------------------------------------------------------------ validation ---
+static int check_config(const sere_config* c) {
+  if (c == nullptr) return SERE_ERR_NULL_PTR;
+  if (c->dtype != SERE_F32 && c->dtype != SERE_BF16) return SERE_ERR_BAD_DTYPE;
+  if (c->flags != 0) return SERE_ERR_BAD_FLAGS;
+  if (c->num_tokens < 1 || c->num_tokens > SERE_MAX_TOKENS) return SERE_ERR_BAD_SHAPE;
+  if (c->hidden < 64 || c->hidden % 64 != 0 || c->hidden > (1 << 16)) return SERE_ERR_BAD_SHAPE;
+  if (c->inter < 64 || c->inter % 64 != 0 || c->inter > (1 << 18)) return SERE_ERR_BAD_SHAPE;
+  if (c->num_experts < 1 || c->num_experts > SERE_MAX_EXPERTS) return SERE_ERR_BAD_SHAPE;
+  if (c->num_shared < 0 || c->num_shared > SERE_MAX_SHARED) return SERE_ERR_BAD_SHAPE;
+  if (c->top_k < 1 || c->top_k > c->num_experts) return SERE_ERR_BAD_TOPK;
+  if (c->select_top_k < 1 || c->select_top_k > c->top_k) return SERE_ERR_BAD_TOPK;
+  if (!std::isfinite(c->threshold)) return SERE_ERR_NONFINITE_THRESHOLD;
+  // the sorted slot list is indexed with int32
+  const int64_t rows = static_cast<int64_t>(c->num_tokens) * (c->top_k + c->num_shared);
+  if (rows > (1 << 24)) return SERE_ERR_BAD_SHAPE;
+  return SERE_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct PtrCheck {
+  int status = SERE_OK;
+  void need(const void* p) {
+    if (status != SERE_OK) return;
+    if (p == nullptr)
+      status = SERE_ERR_NULL_PTR;
+    else if (!aligned16(p))
+      status = SERE_ERR_MISALIGNED;
+  }
+  void optional(const void* p) {
+    if (status == SERE_OK && p != nullptr && !aligned16(p)) status = SERE_ERR_MISALIGNED;
+  }
+};
+
+static void check_route_out(PtrCheck& pc, const sere_route_out* o) {
+  if (o == nullptr) return;
+  pc.optional(o->topk_ids);
+  pc.optional(o->topk_weights);
+  pc.optional(o->rerouted_ids);
+  pc.optional(o->count_before);
+  pc.optional(o->count_after);
+  pc.optional(o->primary_mask);
+  pc.optional(o->num_active);
+  pc.optional(o->expert_offsets);
+  pc.optional(o->sorted_token);
+  pc.optional(o->sorted_slot);
+}
+
+static int check_workspace(const Layout& l, const void* ws, size_t bytes) {
+  if (ws == nullptr) return SERE_ERR_NULL_PTR;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return SERE_ERR_MISALIGNED;
+  if (bytes < l.total) return SERE_ERR_WORKSPACE_TOO_SMALL;
+  return SERE_OK;
+}
+
+// ---------------------------------------------------------------- timing ---
+struct Timing {
+  bool enabled = false;
+  int n = 0;
+  int created = 0;
+  hipEvent_t start[SERE_TIMING_MAX_RECORDS];
+  hipEvent_t stop[SERE_TIMING_MAX_RECORDS];
+  int stage[SERE_TIMING_MAX_RECORDS];
+};
+static Timing g_timing;
+
+struct StageTimer {
+  hipStream_t stream;
+  bool active = false;
+  StageTimer(int stage, hipStream_t s) : stream(s) {
+    Timing& t = g_timing;
+    if (!t.enabled || t.n >= SERE_TIMING_MAX_RECORDS) return;
+    if (t.n >= t.created) {
+      if (hipEventCreate(&t.start[t.created]) != hipSuccess) return;
+      if (hipEventCreate(&t.stop[t.created]) != hipSuccess) {
+        (void)hipEventDestroy(t.start[t.created]);
+        return;
+      }
+      ++t.created;
+    }
+    t.stage[t.n] = stage;
+    active = hipEventRecord(t.start[t.n], stream) == hipSuccess;
+  }
+  ~StageTimer() {
+    if (!active) return;
+    Timing& t = g_timing;
+    if (hipEventRecord(t.stop[t.n], stream) == hipSuccess) ++t.n;
+  }
+};
+
+// --------------------------------------------------------------- launches ---
+struct Pointers {
+  double* logits;
+  int32_t* topk_ids;
+  float* topk_w;
+  RouteArgs route;
+  float* h;
+  float* y;
+};
+
+static Pointers bind(const sere_config& c, const Layout& l, void* workspace, const sere_route_out* o) {
+  char* ws = static_cast<char*>(workspace);
+  auto pick = [&](void* user, size_t off) { return user != nullptr ? user : static_cast<void*>(ws + off); };
+  static const sere_route_out none{};
+  if (o == nullptr) o = &none;
+  Pointers p{};
+  p.logits = reinterpret_cast<double*>(ws + l.logits);
+  p.topk_ids = static_cast<int32_t*>(pick(o->topk_ids, l.topk_ids));
+  p.topk_w = static_cast<float*>(pick(o->topk_weights, l.topk_w));
+  RouteArgs& r = p.route;
+  r.topk_ids = p.topk_ids;
+  r.T = c.num_tokens;
+  r.K = c.top_k;
+  r.M = c.num_experts;
+  r.S = c.select_top_k;
+  r.n_sh = c.num_shared;
+  r.rho = c.threshold;
+  r.rerouted_ids = static_cast<int32_t*>(pick(o->rerouted_ids, l.rerouted));
+  r.count_before = static_cast<int32_t*>(pick(o->count_before, l.cnt_before));
+  r.count_after = static_cast<int32_t*>(pick(o->count_after, l.cnt_after));
+  r.primary_mask = static_cast<int32_t*>(pick(o->primary_mask, l.primary));
+  r.num_active = static_cast<int32_t*>(pick(o->num_active, l.num_active));
+  r.expert_offsets = static_cast<int32_t*>(pick(o->expert_offsets, l.offsets));
+  r.sorted_token = reinterpret_cast<int32_t*>(ws + l.sorted_token);  // holds shared rows too
+  r.sorted_slot = static_cast<int32_t*>(pick(o->sorted_slot, l.sorted_slot));
+  r.slot_pos = reinterpret_cast<int32_t*>(ws + l.slot_pos);
+  r.work_expert = reinterpret_cast<int32_t*>(ws + l.work_expert);
+  r.work_off = reinterpret_cast<int32_t*>(ws + l.work_off);
+  r.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
+  r.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
+  p.h = reinterpret_cast<float*>(ws + l.h);
+  p.y = reinterpret_cast<float*>(ws + l.y);
+  return p;
+}
+
+static int hip_status() { return hipGetLastError() == hipSuccess ? SERE_OK : SERE_ERR_HIP; }
+
+static int launch_router(const sere_config& c, const Pointers& p, const void* hidden,
+                         const void* router_w, hipStream_t s) {
+  {
+    StageTimer tm(SERE_STAGE_ROUTER, s);
+    dim3 grid((c.num_experts + 15) / 16, c.num_tokens);
+    if (c.dtype == SERE_F32)
+      hipLaunchKernelGGL(router_logits_kernel<SERE_F32>, grid, dim3(256), 0, s, hidden, router_w, p.logits,
+                         c.num_tokens, c.num_experts, c.hidden, static_cast<int32_t*>(nullptr));
+    else
+      hipLaunchKernelGGL(router_logits_kernel<SERE_BF16>, grid, dim3(256), 0, s, hidden, router_w, p.logits,
+                         c.num_tokens, c.num_experts, c.hidden, static_cast<int32_t*>(nullptr));
+  }
+  return hip_status();
+}
+
+static int launch_route(const sere_config& c, const Pointers& p, bool with_topk, hipStream_t s,
+                        const sere_route_out* o, size_t sorted_token_bytes) {
+  {
+    StageTimer tm(SERE_STAGE_ROUTE, s);
+    if (with_topk)
+      hipLaunchKernelGGL(topk_gate_kernel, dim3((c.num_tokens + 3) / 4), dim3(256), 0, s, p.logits, p.topk_ids,
+                         p.topk_w, c.num_tokens, c.num_experts, c.top_k);
+    hipLaunchKernelGGL(route_kernel, dim3(1), dim3(kRouteThreads), 0, s, p.route);
+    // the internal sorted_token list also carries the shared experts' rows; a
+    // caller-visible copy holds the routed part only
+    if (o != nullptr && o->sorted_token != nullptr)
+      (void)hipMemcpyAsync(o->sorted_token, p.route.sorted_token, sorted_token_bytes, hipMemcpyDeviceToDevice, s);
+  }
+  return hip_status();
+}
+
+template <int DT>
+static void launch_ffn_t(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
+                         hipStream_t s) {
+  const int max_work = c.num_experts + c.num_shared;
+  {
+    StageTimer tm(SERE_STAGE_GATE_UP, s);
+    hipLaunchKernelGGL(ffn_gateup_generic<DT>, dim3((c.inter + kGenJB - 1) / kGenJB, max_work), dim3(256), 0, s, f);
+  }
+  {
+    StageTimer tm(SERE_STAGE_DOWN, s);
+    hipLaunchKernelGGL(ffn_down_generic<DT>, dim3((c.hidden + kGenRB - 1) / kGenRB, max_work), dim3(256), 0, s, f);
+  }
+  {
+    StageTimer tm(SERE_STAGE_COMBINE, s);
+    CombineArgs ca{p.y, p.topk_w, p.route.slot_pos, out, c.num_tokens, c.hidden, c.top_k, c.num_shared, l.ksplit, l.rows};
+    hipLaunchKernelGGL(combine_kernel<DT>, dim3((c.hidden + 255) / 256, c.num_tokens), dim3(256), 0, s, ca);
+  }
+}
+
+static int decode(const sere_config* cfg, const void* hidden, const void* router_w, const void* w_gate_up,
+                  const void* w_down, const void* shared_gate_up, const void* shared_down, const float* sim,
+                  void* out, const sere_route_out* dbg, void* workspace, size_t workspace_bytes, void* stream,
+                  bool reroute) {
+  int st = check_config(cfg);
+  if (st != SERE_OK) return st;
+  PtrCheck pc;
+  pc.need(hidden);
+  pc.need(router_w);
+  pc.need(w_gate_up);
+  pc.need(w_down);
+  pc.need(out);
+  if (reroute) pc.need(sim);
+  if (cfg->num_shared > 0) {
+    pc.need(shared_gate_up);
+    pc.need(shared_down);
+  }
+  check_route_out(pc, dbg);
+  if (pc.status != SERE_OK) return pc.status;
+  const Layout l = make_layout(*cfg);
+  st = check_workspace(l, workspace, workspace_bytes);
+  if (st != SERE_OK) return st;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Pointers p = bind(*cfg, l, workspace, dbg);
+  p.route.sim = sim;
+  p.route.reroute = reroute ? 1 : 0;
+  if (!reroute) p.route.S = cfg->top_k;  // every slot is a primary slot: identity map
+  st = launch_router(*cfg, p, hidden, router_w, s);
+  if (st != SERE_OK) return st;
+  st = launch_route(*cfg, p, true, s, dbg, static_cast<size_t>(cfg->num_tokens) * cfg->top_k * 4);
+  if (st != SERE_OK) return st;
+
+  FfnArgs f{};
+  f.hidden = hidden;
+  f.w_gate_up = w_gate_up;
+  f.w_down = w_down;
+  f.shared_gate_up = shared_gate_up;
+  f.shared_down = shared_down;
+  f.sorted_token = p.route.sorted_token;
+  f.work_expert = p.route.work_expert;
+  f.work_off = p.route.work_off;
+  f.work_cnt = p.route.work_cnt;
+  f.n_work = p.route.n_work;
+  f.h = p.h;
+  f.y = p.y;
+  f.T = cfg->num_tokens;
+  f.dh = cfg->hidden;
+  f.dm = cfg->inter;
+  f.M = cfg->num_experts;
+  f.K = cfg->top_k;
+  f.n_sh = cfg->num_shared;
+  f.ksplit = l.ksplit;
+  f.rows = l.rows;
+  if (cfg->dtype == SERE_F32)
+    launch_ffn_t<SERE_F32>(*cfg, l, p, f, out, s);
+  else
+    launch_ffn_t<SERE_BF16>(*cfg, l, p, f, out, s);
+  return hip_status();
+}
+
+}  // namespace sere
+
+using namespace sere;
+
+extern "C" {
+
+size_t sere_workspace_bytes(const sere_config* cfg) {
+  if (check_config(cfg) != SERE_OK) return 0;
+  return make_layout(*cfg).total;
+}
+
+int sere_route(const sere_config* cfg, const void* hidden, const void* router_w, const float* sim,
+               const sere_route_out* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != SERE_OK) return st;
+  PtrCheck pc;
+  pc.need(hidden);
+  pc.need(router_w);
+  pc.need(sim);
+  check_route_out(pc, out);
+  if (pc.status != SERE_OK) return pc.status;
+  const Layout l = make_layout(*cfg);
+  st = check_workspace(l, workspace, workspace_bytes);
+  if (st != SERE_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  Pointers p = bind(*cfg, l, workspace, out);
+  p.route.sim = sim;
+  p.route.reroute = 1;
+  st = launch_router(*cfg, p, hidden, router_w, s);
+  if (st != SERE_OK) return st;
+  return launch_route(*cfg, p, true, s, out, static_cast<size_t>(cfg->num_tokens) * cfg->top_k * 4);
+}
+
+int sere_reroute(const sere_config* cfg, const int32_t* topk_ids, const float* sim, const sere_route_out* out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != SERE_OK) return st;
+  PtrCheck pc;
+  pc.need(topk_ids);
+  pc.need(sim);
+  check_route_out(pc, out);
+  if (pc.status != SERE_OK) return pc.status;
+  const Layout l = make_layout(*cfg);
+  st = check_workspace(l, workspace, workspace_bytes);
+  if (st != SERE_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  sere_route_out o{};
+  if (out != nullptr) o = *out;
+  o.topk_ids = nullptr;
+  o.topk_weights = nullptr;
+  Pointers p = bind(*cfg, l, workspace, &o);
+  p.route.topk_ids = topk_ids;
+  p.route.sim = sim;
+  p.route.reroute = 1;
+  return launch_route(*cfg, p, false, s, &o, static_cast<size_t>(cfg->num_tokens) * cfg->top_k * 4);
+}
+
+int sere_moe_decode(const sere_config* cfg, const void* hidden, const void* router_w, const void* w_gate_up,
+                    const void* w_down, const void* shared_gate_up, const void* shared_down, const float* sim,
+                    void* out, const sere_route_out* dbg, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
+  return decode(cfg, hidden, router_w, w_gate_up, w_down, shared_gate_up, shared_down, sim, out, dbg, workspace,
+                workspace_bytes, hip_stream, true);
+}
+
+int sere_moe_decode_baseline(const sere_config* cfg, const void* hidden, const void* router_w,
+                             const void* w_gate_up, const void* w_down, const void* shared_gate_up,
+                             const void* shared_down, void* out, const sere_route_out* dbg, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  return decode(cfg, hidden, router_w, w_gate_up, w_down, shared_gate_up, shared_down, nullptr, out, dbg,
+                workspace, workspace_bytes, hip_stream, false);
+}
+
+int sere_stage_timing(int enable) {
+  g_timing.enabled = enable != 0;
+  g_timing.n = 0;
+  return SERE_OK;
+}
+
+int sere_stage_timing_read(double* total_ms, int32_t* launches) {
+  if (total_ms == nullptr || launches == nullptr) return SERE_ERR_NULL_PTR;
+  for (int i = 0; i < SERE_NUM_STAGES; ++i) {
+    total_ms[i] = 0.0;
+    launches[i] = 0;
+  }
+  Timing& t = g_timing;
+  int status = SERE_OK;
+  for (int i = 0; i < t.n; ++i) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(t.stop[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms, t.start[i], t.stop[i]) != hipSuccess) {
+      status = SERE_ERR_HIP;
+      continue;
+    }
+    total_ms[t.stage[i]] += ms;
+    launches[t.stage[i]] += 1;
+  }
+  t.n = 0;
+  return status;
+}
+
+const char* sere_status_string(int status) {
+  switch (status) {
+    case SERE_OK: return "ok";
+    case SERE_ERR_NULL_PTR: return "a required pointer is NULL";
+    case SERE_ERR_BAD_SHAPE: return "a size is outside the supported range";
+    case SERE_ERR_BAD_TOPK: return "top_k > num_experts or select_top_k outside [1, top_k]";
+    case SERE_ERR_BAD_DTYPE: return "dtype is neither SERE_F32 nor SERE_BF16";
+    case SERE_ERR_MISALIGNED: return "a pointer is not sufficiently aligned";
+    case SERE_ERR_WORKSPACE_TOO_SMALL: return "workspace is smaller than sere_workspace_bytes()";
+    case SERE_ERR_BAD_FLAGS: return "flags must be 0";
+    case SERE_ERR_NONFINITE_THRESHOLD: return "threshold is NaN or infinite";
+    case SERE_ERR_HIP: return "a HIP call reported an error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+"""Moving a generated workload into HBM and calling the library on it.
+
+Only plumbing: numpy storage arrays become torch device tensors (bf16 bit
+patterns are reinterpreted, never converted), buffers are allocated, and the
+C-ABI entry points are called through the binding.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+from . import binding as B
+from .workloads import BF16, F32, Workload
+
+
+def to_device(a: Optional[np.ndarray], dtype: int, device="cuda"):
+    """numpy storage array -> torch tensor on `device` (bf16 for uint16 bit patterns)."""
+    import torch
+    if a is None:
+        return None
+    if dtype == F32:
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint16).view(np.int16)).to(device)
+    return t.view(torch.bfloat16)
+
+
+def to_host(t, dtype: int) -> np.ndarray:
+    """torch tensor -> numpy storage array (uint16 bit patterns for bf16)."""
+    import torch
+    if dtype == F32:
+        return t.detach().cpu().numpy()
+    return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@dataclass
+class DeviceLayer:
+    """One MoE layer's tensors resident in HBM plus the call-time buffers."""
+    spec: object
+    hidden: object
+    router_w: object
+    w_gate_up: object
+    w_down: object
+    shared_gate_up: object
+    shared_down: object
+    sim: object
+    out: object
+    workspace: object
+    route: B.RouteBuffers
+    cfg: B.sere_config
+
+    @staticmethod
+    def from_workload(wl: Workload, sim: np.ndarray, S: int, rho: float, device="cuda",
+                      weights=None) -> "DeviceLayer":
+        """`weights` lets several DeviceLayers (other batches / settings) share one
+        resident copy of the expert tensors: (router_w, w_gate_up, w_down, sgu, sdn)."""
+        import torch
+        sp = wl.spec
+        cfg = B.make_config(wl.hidden.shape[0], sp.hidden, sp.experts, sp.top_k, sp.inter,
+                            sp.shared, sp.dtype, S, rho)
+        if weights is None:
+            weights = (to_device(wl.router_w, sp.dtype, device), to_device(wl.w_gate_up, sp.dtype, device),
+                       to_device(wl.w_down, sp.dtype, device),
+                       to_device(wl.shared_gate_up, sp.dtype, device),
+                       to_device(wl.shared_down, sp.dtype, device))
+        tdt = torch.float32 if sp.dtype == F32 else torch.bfloat16
+        return DeviceLayer(
+            sp, to_device(wl.hidden, sp.dtype, device), *weights,
+            torch.from_numpy(np.ascontiguousarray(sim, dtype=np.float32)).to(device),
+            torch.zeros((wl.hidden.shape[0], sp.hidden), dtype=tdt, device=device),
+            B.alloc_workspace(cfg, device), B.RouteBuffers.allocate(cfg, device), cfg)
+
+    def weights(self):
+        return (self.router_w, self.w_gate_up, self.w_down, self.shared_gate_up, self.shared_down)
+
+    def set_knobs(self, S: int, rho: float) -> None:
+        self.cfg.select_top_k = S
+        self.cfg.threshold = rho
+
+    def run_route(self, stream=None, with_outputs=True) -> None:
+        B.sere_route(self.cfg, self.hidden, self.router_w, self.sim,
+                     self.route if with_outputs else None, self.workspace, stream)
+
+    def run_decode(self, stream=None, with_outputs=True) -> None:
+        B.sere_moe_decode(self.cfg, self.hidden, self.router_w, self.w_gate_up, self.w_down,
+                          self.shared_gate_up, self.shared_down, self.sim, self.out,
+                          self.route if with_outputs else None, self.workspace, stream)
+
+    def run_baseline(self, stream=None, with_outputs=True) -> None:
+        B.sere_moe_decode_baseline(self.cfg, self.hidden, self.router_w, self.w_gate_up,
+                                   self.w_down, self.shared_gate_up, self.shared_down, self.out,
+                                   self.route if with_outputs else None, self.workspace, stream)
+
+    def routing_to_host(self) -> dict:
+        import torch
+        torch.cuda.synchronize()
+        return {n: getattr(self.route, n).cpu().numpy() for n, _ in B.sere_route_out._fields_}
+
+    def out_to_host_f64(self) -> np.ndarray:
+        import torch
+        torch.cuda.synchronize()
+        return self.out.detach().to(torch.float64).cpu().numpy()

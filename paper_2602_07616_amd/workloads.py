@@ -194,7 +194,7 @@ SPECS: Dict[str, LayerSpec] = {
                               grid=((2, 0.0), (2, 0.3), (1, 0.0), (1, 0.3))),
     # Mixtral-8x7B-shaped layer: few, very large experts
     "mixtral_b64": LayerSpec("mixtral_b64", BF16, 4096, 8, 2, 14336, 0, 64, 1005, 1005,
-                             calib_tokens=16,
+                             calib_tokens=8,
                              grid=((1, 0.0), (1, 0.3))),
     # Qwen1.5-MoE-A2.7B-shaped layer (60 experts, top-4, 4 shared).  The paper
     # gives no per-expert width; 1408 is this build's choice.

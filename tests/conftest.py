@@ -37,8 +37,8 @@ def get_similarity(name):
     import oracle
     from paper_2602_07616_amd import workloads
     spec = workloads.SPECS[name]
-    key = (spec.weight_seed, spec.hidden_seed if spec.clusters else 0, spec.experts,
-           spec.hidden, spec.inter, spec.calib_batches, spec.calib_tokens, spec.clusters)
+    key = (spec.weight_seed, spec.hidden_seed, spec.experts, spec.hidden, spec.inter,
+           spec.calib_batches, spec.calib_tokens, spec.clusters)
     if key not in _sims:
         wl = get_workload(name)
         sim = oracle.similarity_frobenius(wl.calib, wl.w_gate_up, wl.w_down, spec.dtype)

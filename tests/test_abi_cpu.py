@@ -1,0 +1,113 @@
+"""CPU-only: the C-ABI library loads, exports every symbol the header declares,
+and rejects bad arguments before touching the device (no compute call here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_07616_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sere.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sere_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol():
+    lib = B.load()
+    names = declared_functions()
+    assert {"sere_route", "sere_moe_decode", "sere_moe_decode_baseline", "sere_reroute",
+            "sere_workspace_bytes", "sere_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"libsere.so does not export {n}"
+
+
+def test_struct_sizes_match_header():
+    assert ctypes.sizeof(B.sere_config) == 40
+    assert ctypes.sizeof(B.sere_route_out) == 10 * ctypes.sizeof(ctypes.c_void_p)
+
+
+def good():
+    return B.make_config(32, 2048, 128, 8, 768, 0, B.SERE_BF16, 2, 0.5)
+
+
+def test_workspace_size_and_status_strings():
+    assert B.sere_workspace_bytes(good()) > 0
+    c = good(); c.num_shared = 2
+    assert B.sere_workspace_bytes(c) > B.sere_workspace_bytes(good())
+    assert B.load().sere_workspace_bytes(None) == 0
+    for s in range(0, -10, -1):
+        assert B.sere_status_string(s) and B.sere_status_string(s) != "unknown status"
+    assert B.sere_status_string(-99) == "unknown status"
+
+
+BAD_CONFIGS = [
+    ("num_tokens", 0, B.SERE_ERR_BAD_SHAPE), ("num_tokens", 65537, B.SERE_ERR_BAD_SHAPE),
+    ("hidden", 0, B.SERE_ERR_BAD_SHAPE), ("hidden", 2050, B.SERE_ERR_BAD_SHAPE),
+    ("inter", 100, B.SERE_ERR_BAD_SHAPE), ("num_experts", 0, B.SERE_ERR_BAD_SHAPE),
+    ("num_experts", 257, B.SERE_ERR_BAD_SHAPE), ("num_shared", -1, B.SERE_ERR_BAD_SHAPE),
+    ("num_shared", 17, B.SERE_ERR_BAD_SHAPE), ("top_k", 0, B.SERE_ERR_BAD_TOPK),
+    ("top_k", 129, B.SERE_ERR_BAD_TOPK), ("select_top_k", 0, B.SERE_ERR_BAD_TOPK),
+    ("select_top_k", 9, B.SERE_ERR_BAD_TOPK), ("dtype", 2, B.SERE_ERR_BAD_DTYPE),
+    ("flags", 1, B.SERE_ERR_BAD_FLAGS), ("threshold", float("nan"), B.SERE_ERR_NONFINITE_THRESHOLD),
+    ("threshold", float("inf"), B.SERE_ERR_NONFINITE_THRESHOLD),
+]
+FAKE = 0x10000  # aligned, non-NULL, never dereferenced: validation fails first
+
+
+def call_all(cfg, ptr=FAKE, ws=FAKE, ws_bytes=1 << 40, sim=FAKE, out=FAKE):
+    lib = B.load()
+    c = ctypes.byref(cfg)
+    return [
+        lib.sere_route(c, ptr, ptr, sim, None, ws, ws_bytes, None),
+        lib.sere_reroute(c, ptr, sim, None, ws, ws_bytes, None),
+        lib.sere_moe_decode(c, ptr, ptr, ptr, ptr, None, None, sim, out, None, ws, ws_bytes, None),
+        lib.sere_moe_decode_baseline(c, ptr, ptr, ptr, ptr, None, None, out, None, ws, ws_bytes, None),
+    ]
+
+
+@pytest.mark.parametrize("field,value,status", BAD_CONFIGS)
+def test_bad_config_rejected(field, value, status):
+    cfg = good()
+    setattr(cfg, field, value)
+    assert B.sere_workspace_bytes(cfg) == 0
+    assert call_all(cfg) == [status] * 4
+
+
+def test_bad_pointers_rejected():
+    cfg = good()
+    lib = B.load()
+    assert lib.sere_route(None, FAKE, FAKE, FAKE, None, FAKE, 1 << 40, None) == B.SERE_ERR_NULL_PTR
+    assert call_all(cfg, ptr=0) == [B.SERE_ERR_NULL_PTR] * 4
+    assert call_all(cfg, ptr=FAKE + 4) == [B.SERE_ERR_MISALIGNED] * 4
+    assert call_all(cfg, ws=0) == [B.SERE_ERR_NULL_PTR] * 4
+    assert call_all(cfg, ws=FAKE + 16) == [B.SERE_ERR_MISALIGNED] * 4
+    need = B.sere_workspace_bytes(cfg)
+    assert call_all(cfg, ws_bytes=need - 1) == [B.SERE_ERR_WORKSPACE_TOO_SMALL] * 4
+    # sim is required where re-routing happens, not for the baseline
+    got = call_all(cfg, sim=0, ws_bytes=need - 1)
+    assert got[:3] == [B.SERE_ERR_NULL_PTR] * 3 and got[3] == B.SERE_ERR_WORKSPACE_TOO_SMALL
+    # shared experts: weights required iff num_shared > 0
+    cfg.num_shared = 2
+    c = ctypes.byref(cfg)
+    assert lib.sere_moe_decode(c, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, None, FAKE, 0,
+                               None) == B.SERE_ERR_NULL_PTR
+    assert lib.sere_moe_decode(c, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 0,
+                               None) == B.SERE_ERR_WORKSPACE_TOO_SMALL
+    # a misaligned optional output is refused too
+    o = B.sere_route_out()
+    o.count_after = FAKE + 2
+    assert lib.sere_route(ctypes.byref(good()), FAKE, FAKE, FAKE, ctypes.byref(o), FAKE, 1 << 40,
+                          None) == B.SERE_ERR_MISALIGNED
+
+
+def test_binding_raises_on_error():
+    cfg = good()
+    cfg.top_k = 500
+    with pytest.raises(B.SereError) as e:
+        B._check(B.load().sere_route(ctypes.byref(cfg), FAKE, FAKE, FAKE, None, FAKE, 0, None))
+    assert e.value.status == B.SERE_ERR_BAD_TOPK

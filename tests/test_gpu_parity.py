@@ -1,0 +1,330 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
+same seeded inputs.  Integers (routing indices, counts, masks, offsets, sorted
+lists) must match bit for bit; layer outputs within the stated tolerance."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_07616_amd import workloads as wk
+from . import pins
+from .conftest import get_similarity, get_workload
+
+pytestmark = pytest.mark.gpu
+
+# bf16 layers: the bound the task states (max-abs 2e-2, rel-L2 1e-2, fp32
+# accumulation).  fp32 layers: sums of <= 256 / 128 fp32 products of magnitude
+# <= ~0.1 round to ~1e-7 absolute; 1e-5 leaves two orders of margin.
+TOL = {wk.BF16: (2e-2, 1e-2), wk.F32: (1e-5, 1e-5)}
+
+INT_FIELDS = ("topk_ids", "rerouted_ids", "count_before", "count_after", "primary_mask",
+              "expert_offsets", "sorted_token", "sorted_slot")
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2602_07616_amd import binding, device
+    binding.load()
+    return device
+
+
+_layers = {}
+
+
+def device_layer(dev, name, tokens=None):
+    """One resident copy of each workload per test session."""
+    key = (name, tokens)
+    if key not in _layers:
+        wl = get_workload(name, tokens)
+        base = _layers.get((name, None))
+        weights = base[1].weights() if base is not None else None
+        sim = get_similarity(name)
+        _layers[key] = (wl, dev.DeviceLayer.from_workload(wl, sim, 1, 0.0, weights=weights), sim)
+    return _layers[key]
+
+
+def check_routing(got, ref, cfg):
+    for f in INT_FIELDS:
+        want = {"expert_offsets": ref.offsets}.get(f, getattr(ref, f, None))
+        assert np.array_equal(got[f], np.asarray(want).reshape(got[f].shape)), f
+    assert got["num_active"].tolist() == [ref.n_active_before, ref.n_active_after]
+    assert np.allclose(got["topk_weights"], ref.topk_weights, rtol=1e-6, atol=1e-7)
+
+
+def elementwise_bound(want, dtype):
+    """Per-element absolute bound.  The stated 2e-2 everywhere, except where a
+    bf16 OUTPUT cannot meet it: for |y| >= 8 half a bf16 ulp is already 2^-5 =
+    0.031, so there the bound is one rounding step (half an ulp of the exact
+    value) plus a quarter."""
+    max_abs, _ = TOL[dtype]
+    if dtype != wk.BF16:
+        return np.full(want.shape, max_abs)
+    mag = np.maximum(np.abs(want), 1e-30)
+    half_ulp = np.exp2(np.floor(np.log2(mag)) - 8)
+    return np.maximum(max_abs, 1.25 * half_ulp)
+
+
+def check_output(got, want, dtype, what=""):
+    _, rel = TOL[dtype]
+    diff = np.abs(got - want)
+    err = diff.max()
+    rl2 = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
+    assert np.isfinite(got).all(), what
+    worst = (diff / elementwise_bound(want, dtype)).max()
+    assert worst <= 1.0 and rl2 <= rel, f"{what}: max_abs {err:.3e} rel_l2 {rl2:.3e} worst/bound {worst:.2f}"
+    return err, rl2
+
+
+_oracle_cache = {}
+
+
+def oracle_route(wl, sim, S, rho, key):
+    k = ("route", key, S, rho)
+    if k not in _oracle_cache:
+        sp = wl.spec
+        r = oracle.route(wl.hidden, wl.router_w, sp.dtype, sp.top_k, sim, S, rho)
+        assert r.min_gap > 1e-9, "seed gives a near-tie in the router ordering"
+        _oracle_cache[k] = r
+    return _oracle_cache[k]
+
+
+def oracle_output(wl, ids, weights, key, tokens=None):
+    """fp64 layer output for a token-to-expert map (optionally a token subset)."""
+    sel = np.arange(wl.hidden.shape[0]) if tokens is None else np.asarray(tokens)
+    k = ("out", key, ids[sel].tobytes(), sel.tobytes())
+    if k not in _oracle_cache:
+        sp = wl.spec
+        _oracle_cache[k] = oracle.moe_layer(
+            np.ascontiguousarray(wl.hidden[sel]), wl.w_gate_up, wl.w_down, wl.shared_gate_up,
+            wl.shared_down, sp.dtype, np.ascontiguousarray(ids[sel]),
+            np.ascontiguousarray(weights[sel]))
+    return _oracle_cache[k]
+
+
+FULL = ["tiny", "qwen3_b32", "qwen3_b128", "dsv2lite_b64", "mixtral_b64", "qwen15_b32"]
+# layers whose full oracle output is too slow to compute for every token
+SAMPLED = {"mixtral_b64": [0, 7, 13, 21, 30, 42, 55, 63]}
+
+
+def grid_of(name):
+    sp = wk.SPECS[name]
+    return list(sp.grid) + [(sp.top_k, 0.0)]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_route_parity(dev, name):
+    wl, layer, sim = device_layer(dev, name)
+    for S, rho in grid_of(name):
+        print(f"route {name} S={S} rho={rho}", flush=True)
+        layer.set_knobs(S, rho)
+        layer.run_route()
+        got = layer.routing_to_host()
+        ref = oracle_route(wl, sim, S, rho, name)
+        check_routing(got, ref, layer.cfg)
+        pins.check_reroute_invariants(got["topk_ids"], got["rerouted_ids"], sim, S, rho,
+                                      got["primary_mask"], (got["count_after"] > 0).astype(np.int32),
+                                      got["count_before"], got["count_after"])
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_decode_parity(dev, name):
+    wl, layer, sim = device_layer(dev, name)
+    sp = wl.spec
+    tokens = SAMPLED.get(name)
+    sel = slice(None) if tokens is None else tokens
+    for S, rho in grid_of(name):
+        print(f"decode {name} S={S} rho={rho}", flush=True)
+        layer.set_knobs(S, rho)
+        layer.out.zero_()
+        layer.run_decode()
+        got_r = layer.routing_to_host()
+        ref = oracle_route(wl, sim, S, rho, name)
+        check_routing(got_r, ref, layer.cfg)
+        want = oracle_output(wl, ref.rerouted_ids, ref.topk_weights, name, tokens)
+        err = check_output(layer.out_to_host_f64()[sel], want, sp.dtype, f"{name} S={S} rho={rho}")
+        print(f"   active {ref.n_active_before}->{ref.n_active_after}  max_abs {err[0]:.2e} rel_l2 {err[1]:.2e}",
+              flush=True)
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_baseline_parity(dev, name):
+    wl, layer, sim = device_layer(dev, name)
+    sp = wl.spec
+    tokens = SAMPLED.get(name)
+    sel = slice(None) if tokens is None else tokens
+    print(f"baseline {name}", flush=True)
+    layer.set_knobs(1, 0.0)          # ignored by the baseline entry point
+    layer.out.zero_()
+    layer.run_baseline()
+    got_r = layer.routing_to_host()
+    ref = oracle_route(wl, sim, sp.top_k, 0.0, name)      # S == K: identity map
+    assert np.array_equal(ref.rerouted_ids, ref.topk_ids)
+    check_routing(got_r, ref, layer.cfg)
+    want = oracle_output(wl, ref.topk_ids, ref.topk_weights, name, tokens)
+    check_output(layer.out_to_host_f64()[sel], want, sp.dtype, f"{name} baseline")
+    # the three ways to disable re-routing agree bit for bit
+    base = layer.out.clone()
+    layer.set_knobs(sp.top_k, 0.0)
+    layer.run_decode()
+    assert (layer.out == base).all()
+    off_diag_max = float(sim[~np.eye(sp.experts, dtype=bool)].max())
+    layer.set_knobs(1, min(1.0, np.nextafter(np.float32(off_diag_max), np.float32(2)).item()))
+    layer.run_decode()
+    assert (layer.out == base).all()
+
+
+def test_batch_sweep_routing(dev):
+    """Qwen3-shaped layer over the batch sizes of the sweep (prefixes of one draw)."""
+    for T in wk.BATCH_SWEEP:
+        wl, layer, sim = device_layer(dev, "qwen3_b128", T)
+        for S, rho in ((2, 0.0), (1, 0.0), (1, 0.5)):
+            print(f"sweep T={T} S={S} rho={rho}", flush=True)
+            layer.set_knobs(S, rho)
+            layer.run_route()
+            check_routing(layer.routing_to_host(), oracle_route(wl, sim, S, rho, ("sweep", T)), layer.cfg)
+
+
+@pytest.mark.parametrize("T", [1, 16, 256])
+def test_batch_sweep_decode(dev, T):
+    wl, layer, sim = device_layer(dev, "qwen3_b128", T)
+    for S, rho in ((1, 0.0), (8, 0.0)):
+        print(f"sweep decode T={T} S={S}", flush=True)
+        layer.set_knobs(S, rho)
+        layer.run_decode()
+        ref = oracle_route(wl, sim, S, rho, ("sweep", T))
+        check_routing(layer.routing_to_host(), ref, layer.cfg)
+        tokens = None if T <= 64 else list(range(0, T, 8))
+        want = oracle_output(wl, ref.rerouted_ids, ref.topk_weights, ("sweep", T), tokens)
+        got = layer.out_to_host_f64()
+        check_output(got if tokens is None else got[tokens], want, wl.spec.dtype, f"T={T} S={S}")
+
+
+# ------------------------------------------------------------ edge cases ---
+def small_case(dev, dtype, T, dh, M, K, dm, n_sh, seed, S, rho, sim=None, mutate=None):
+    spec = wk.custom_spec(f"edge{seed}", dtype, dh, M, K, dm, n_sh, T, seed, weight_std=0.02,
+                          calib_batches=1, calib_tokens=4)
+    wl = wk.make_workload(spec)
+    if mutate is not None:
+        mutate(wl)
+    if sim is None:
+        sim = pins.rand_sim(seed, M)
+    layer = dev.DeviceLayer.from_workload(wl, sim, S, rho)
+    return wl, layer, sim
+
+
+EDGE = [
+    # dtype, T, dh, M, K, dm, n_sh, S, rho
+    (wk.BF16, 37, 512, 24, 4, 320, 1, 1, 0.3),     # ragged token count, several tiles, shared expert
+    (wk.BF16, 1, 256, 8, 3, 64, 0, 1, 0.0),        # single token
+    (wk.BF16, 5, 128, 4, 4, 128, 0, 2, 0.0),       # M == K: every expert active
+    (wk.F32, 19, 192, 10, 3, 192, 2, 1, 0.5),      # fp32 with shared experts
+    (wk.F32, 3, 64, 1, 1, 64, 0, 1, 0.0),          # one expert, smallest sizes
+    (wk.BF16, 70, 64, 256, 5, 64, 0, 2, 0.4),      # maximum expert count
+    (wk.BF16, 130, 256, 6, 2, 128, 0, 1, 0.0),     # many tokens per expert (> one tile)
+    (wk.BF16, 9, 1024, 12, 6, 2112, 0, 3, 0.2),    # inter not a power of two, wide
+]
+
+
+@pytest.mark.parametrize("case", EDGE, ids=lambda c: "x".join(str(v) for v in c))
+def test_edge_cases(dev, case):
+    dtype, T, dh, M, K, dm, n_sh, S, rho = case
+    print(f"edge {case}", flush=True)
+    wl, layer, sim = small_case(dev, dtype, T, dh, M, K, dm, n_sh, 7000 + T + M, S, rho)
+    ref = oracle.layer(wl.hidden, wl.router_w, wl.w_gate_up, wl.w_down, wl.shared_gate_up,
+                       wl.shared_down, dtype, K, sim, S, rho)
+    assert ref.min_gap > 1e-9
+    layer.run_decode()
+    check_routing(layer.routing_to_host(), ref, layer.cfg)
+    check_output(layer.out_to_host_f64(), ref.out_sere, dtype, "sere")
+    layer.run_baseline()
+    check_output(layer.out_to_host_f64(), ref.out_base, dtype, "baseline")
+    # without the optional routing outputs the result is the same
+    layer.run_decode()
+    a = layer.out.clone()
+    layer.out.zero_()
+    layer.run_decode(with_outputs=False)
+    assert (layer.out == a).all()
+
+
+def test_identical_tokens_and_duplicate_router_rows(dev):
+    """Exact ties: all tokens equal, and router rows 3 and 5 bit-identical, so
+    their logits tie exactly and the lower index must rank first."""
+    def mutate(wl):
+        wl.hidden[:] = wl.hidden[0]
+        wl.router_w[5] = wl.router_w[3]
+    wl, layer, sim = small_case(dev, wk.BF16, 6, 256, 8, 8, 64, 0, 9001, 2, 0.0, mutate=mutate)
+    logits = oracle.router_logits(wl.hidden, wl.router_w, wk.BF16)
+    assert np.all(logits[:, 3] == logits[:, 5])
+    ids, w, _ = oracle.topk_gate(logits, 8)
+    layer.run_route()
+    got = layer.routing_to_host()
+    assert np.array_equal(got["topk_ids"], ids)
+    pos3 = np.argwhere(ids == 3)[:, 1]
+    pos5 = np.argwhere(ids == 5)[:, 1]
+    assert np.all(pos5 == pos3 + 1)
+    ref_ids, final, _, _ = oracle.reroute_sets(ids, sim, 2, 0.0)
+    assert np.array_equal(got["rerouted_ids"], ref_ids)
+    assert got["num_active"].tolist() == [8, 2]
+
+
+def test_reroute_entry_point(dev):
+    """sere_reroute (indices in, indices out) on random maps: quantised, constant
+    and asymmetric similarity matrices, thresholds on exact similarity values."""
+    import torch
+    from paper_2602_07616_amd import binding as B
+    for c in range(24):
+        M = [4, 16, 60, 128, 256][c % 5]
+        K = min(M, [2, 4, 8, 6][c % 4])
+        T = [1, 7, 64, 300][c % 4]
+        S = 1 + c % K
+        levels = [0, 4, 1][c % 3]
+        sim = pins.rand_sim(5000 + c, M, levels=levels, symmetric=bool(c % 2))
+        if levels == 1:
+            sim[:] = 0.25
+        rho = [0.0, 0.25, 0.5, 0.75, -1.0, 1.0][c % 6]
+        ids = pins.rand_ids(6000 + c, T, K, M)
+        print(f"reroute case {c}: T={T} K={K} M={M} S={S} rho={rho}", flush=True)
+        cfg = B.make_config(T, 64, M, K, 64, 0, B.SERE_BF16, S, rho)
+        bufs = B.RouteBuffers.allocate(cfg)
+        ws = B.alloc_workspace(cfg)
+        B.sere_reroute(cfg, torch.from_numpy(ids).cuda(), torch.from_numpy(sim).cuda(), bufs, ws)
+        torch.cuda.synchronize()
+        want, final, _, _ = oracle.reroute_sets(ids, sim, S, rho)
+        cnt, offs, tok, slot, n_after = oracle.compact(want, M)
+        assert np.array_equal(bufs.rerouted_ids.cpu().numpy(), want)
+        assert np.array_equal(bufs.count_after.cpu().numpy(), cnt)
+        assert np.array_equal(bufs.expert_offsets.cpu().numpy(), offs)
+        assert np.array_equal(bufs.sorted_token.cpu().numpy(), tok)
+        assert np.array_equal(bufs.sorted_slot.cpu().numpy(), slot)
+        assert np.array_equal(bufs.primary_mask.cpu().numpy(), oracle.primary_mask(ids, S, M))
+        assert bufs.num_active.cpu().numpy()[1] == n_after
+        assert np.array_equal((cnt > 0).astype(np.int32), final)
+        assert (bufs.topk_ids.cpu().numpy() == -1).all()      # not written by this entry point
+
+
+def test_two_runs_are_bit_identical(dev):
+    wl, layer, sim = device_layer(dev, "qwen3_b32")
+    layer.set_knobs(1, 0.0)
+    layer.run_decode()
+    a, ra = layer.out.clone(), layer.routing_to_host()
+    layer.out.zero_()
+    layer.workspace.fill_(0x5A)            # stale workspace contents must not matter
+    layer.run_decode()
+    rb = layer.routing_to_host()
+    assert (layer.out == a).all()
+    for k in ra:
+        assert np.array_equal(ra[k], rb[k]), k
+
+
+def test_stage_timing_reports_every_stage(dev):
+    from paper_2602_07616_amd import binding as B
+    wl, layer, sim = device_layer(dev, "tiny")
+    layer.set_knobs(1, 0.0)
+    B.sere_stage_timing(True)
+    for _ in range(3):
+        layer.run_decode(with_outputs=False)
+    ms, n = B.sere_stage_timing_read()
+    B.sere_stage_timing(False)
+    assert all(n[s] == 3 for s in B.STAGES), n
+    assert all(ms[s] > 0 for s in B.STAGES), ms
