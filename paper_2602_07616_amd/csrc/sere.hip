@@ -8,6 +8,7 @@
 
 #include "common.hpp"
 #include "ffn_generic.hpp"
+#include "ffn_mfma.hpp"
 #include "route_kernels.hpp"
 
 namespace sere {
@@ -22,7 +23,11 @@ struct Layout {
 
 static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
-static int down_ksplit(const sere_config& c) { return 1; }
+// bf16 down projection: d_m is cut into slices of at most 2048 so that one block
+// streams ~256 KB of weights whatever the expert width
+static int down_ksplit(const sere_config& c) {
+  return c.dtype == SERE_BF16 ? (c.inter + 2047) / 2048 : 1;
+}
 
 static Layout make_layout(const sere_config& c) {
   Layout l{};
@@ -228,23 +233,42 @@ static int launch_route(const sere_config& c, const Pointers& p, bool with_topk,
   return hip_status();
 }
 
-template <int DT>
-static void launch_ffn_t(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
-                         hipStream_t s) {
+static void launch_combine(const sere_config& c, const Layout& l, const Pointers& p, void* out, hipStream_t s) {
+  StageTimer tm(SERE_STAGE_COMBINE, s);
+  CombineArgs ca{p.y, p.topk_w, p.route.slot_pos, out, c.num_tokens, c.hidden, c.top_k, c.num_shared, l.ksplit, l.rows};
+  const dim3 grid((c.hidden + 255) / 256, c.num_tokens);
+  if (c.dtype == SERE_F32)
+    hipLaunchKernelGGL(combine_kernel<SERE_F32>, grid, dim3(256), 0, s, ca);
+  else
+    hipLaunchKernelGGL(combine_kernel<SERE_BF16>, grid, dim3(256), 0, s, ca);
+}
+
+// fp32 layers: vector-ALU kernels.  bf16 layers: matrix-core kernels.
+static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
+                       hipStream_t s) {
   const int max_work = c.num_experts + c.num_shared;
-  {
-    StageTimer tm(SERE_STAGE_GATE_UP, s);
-    hipLaunchKernelGGL(ffn_gateup_generic<DT>, dim3((c.inter + kGenJB - 1) / kGenJB, max_work), dim3(256), 0, s, f);
+  if (c.dtype == SERE_F32) {
+    {
+      StageTimer tm(SERE_STAGE_GATE_UP, s);
+      hipLaunchKernelGGL(ffn_gateup_generic<SERE_F32>, dim3((c.inter + kGenJB - 1) / kGenJB, max_work), dim3(256),
+                         0, s, f);
+    }
+    {
+      StageTimer tm(SERE_STAGE_DOWN, s);
+      hipLaunchKernelGGL(ffn_down_generic<SERE_F32>, dim3((c.hidden + kGenRB - 1) / kGenRB, max_work), dim3(256),
+                         0, s, f);
+    }
+  } else {
+    {
+      StageTimer tm(SERE_STAGE_GATE_UP, s);
+      hipLaunchKernelGGL(ffn_gateup_mfma, dim3(c.inter / kMfmaJB, max_work), dim3(256), 0, s, f);
+    }
+    {
+      StageTimer tm(SERE_STAGE_DOWN, s);
+      hipLaunchKernelGGL(ffn_down_mfma, dim3((c.hidden / kMfmaRows) * l.ksplit, max_work), dim3(256), 0, s, f);
+    }
   }
-  {
-    StageTimer tm(SERE_STAGE_DOWN, s);
-    hipLaunchKernelGGL(ffn_down_generic<DT>, dim3((c.hidden + kGenRB - 1) / kGenRB, max_work), dim3(256), 0, s, f);
-  }
-  {
-    StageTimer tm(SERE_STAGE_COMBINE, s);
-    CombineArgs ca{p.y, p.topk_w, p.route.slot_pos, out, c.num_tokens, c.hidden, c.top_k, c.num_shared, l.ksplit, l.rows};
-    hipLaunchKernelGGL(combine_kernel<DT>, dim3((c.hidden + 255) / 256, c.num_tokens), dim3(256), 0, s, ca);
-  }
+  launch_combine(c, l, p, out, s);
 }
 
 static int decode(const sere_config* cfg, const void* hidden, const void* router_w, const void* w_gate_up,
@@ -301,10 +325,7 @@ static int decode(const sere_config* cfg, const void* hidden, const void* router
   f.n_sh = cfg->num_shared;
   f.ksplit = l.ksplit;
   f.rows = l.rows;
-  if (cfg->dtype == SERE_F32)
-    launch_ffn_t<SERE_F32>(*cfg, l, p, f, out, s);
-  else
-    launch_ffn_t<SERE_BF16>(*cfg, l, p, f, out, s);
+  launch_ffn(*cfg, l, p, f, out, s);
   return hip_status();
 }
 
