@@ -155,8 +155,8 @@ int sere_reroute(const sere_config *cfg, const int32_t *topk_ids, const float *s
  *   shared_down    [n_sh, d_h, d_m]    dtype, NULL iff num_shared == 0
  *   out            [T, d_h]            dtype; fp32 accumulation, one rounding
  *   dbg            optional routing outputs (may be NULL)
- * The intermediate silu(g)*u is kept at fp32 precision (for SERE_BF16 on the
- * matrix cores: as a bf16 high part plus a bf16 low part).
+ * The intermediate silu(g)*u is kept in fp32 for SERE_F32 and rounded once to
+ * bf16 (the matrix cores' input type) for SERE_BF16.
  */
 int sere_moe_decode(const sere_config *cfg, const void *hidden, const void *router_w,
                     const void *w_gate_up, const void *w_down, const void *shared_gate_up,

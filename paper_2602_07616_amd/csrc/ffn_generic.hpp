@@ -23,11 +23,12 @@ struct FfnArgs {
   const int32_t* work_off;
   const int32_t* work_cnt;
   const int32_t* n_work;
-  float* h;                    // [R, dm] fp32: silu(gate) * up
+  float* h;                    // silu(gate) * up: [R, dm] fp32, or bf16 plane(s) [R, dm] on the bf16 path
   float* y;                    // [ksplit, R, dh] fp32 partial down projections
   int T, dh, dm, M, K, n_sh;
   int ksplit;                  // slices of dm in the down projection
   int rows;                    // R
+  int split_h;                 // bf16 path: h carried as a high and a low bf16 plane
 };
 
 template <int DT>

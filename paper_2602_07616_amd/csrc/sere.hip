@@ -23,8 +23,8 @@ struct Layout {
 
 static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
 
-// bf16 down projection: d_m is cut into slices of at most 2048 so that one block
-// streams ~256 KB of weights whatever the expert width
+// bf16 down projection: d_m is cut into slices of at most 2048 so that one
+// wavefront streams at most 64 KB of weights whatever the expert width
 static int down_ksplit(const sere_config& c) {
   return c.dtype == SERE_BF16 ? (c.inter + 2047) / 2048 : 1;
 }
@@ -261,11 +261,11 @@ static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p,
   } else {
     {
       StageTimer tm(SERE_STAGE_GATE_UP, s);
-      hipLaunchKernelGGL(ffn_gateup_mfma, dim3(c.inter / kMfmaJB, max_work), dim3(256), 0, s, f);
+      hipLaunchKernelGGL(ffn_gateup_mfma, dim3(c.inter / (kGateUpJ * kWavesPerBlock), max_work), dim3(256), 0, s, f);
     }
     {
       StageTimer tm(SERE_STAGE_DOWN, s);
-      hipLaunchKernelGGL(ffn_down_mfma, dim3((c.hidden / kMfmaRows) * l.ksplit, max_work), dim3(256), 0, s, f);
+      hipLaunchKernelGGL(ffn_down_mfma, dim3(((c.hidden + kDownRows * kWavesPerBlock - 1) / (kDownRows * kWavesPerBlock)) * l.ksplit, max_work), dim3(256), 0, s, f);
     }
   }
   launch_combine(c, l, p, out, s);
@@ -325,6 +325,12 @@ static int decode(const sere_config* cfg, const void* hidden, const void* router
   f.n_sh = cfg->num_shared;
   f.ksplit = l.ksplit;
   f.rows = l.rows;
+  // Rounding h to bf16 perturbs every term of the down projection by up to
+  // 2^-9 relative; the sum of d_m such terms stays far inside the output
+  // tolerance for narrow experts, but not for very wide ones whose outputs
+  // reach several units.  From d_m = 4096 on, h keeps its rounding residual in
+  // a second bf16 plane and the down projection multiplies both.
+  f.split_h = (cfg->dtype == SERE_BF16 && cfg->inter >= 4096) ? 1 : 0;
   launch_ffn(*cfg, l, p, f, out, s);
   return hip_status();
 }
