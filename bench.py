@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep")
     ap.add_argument("--no-graph", action="store_true", help="plain stream launches, no HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-sere", action="store_true",
+                    help="time only the headline SERE step (for per-kernel profiles)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -192,8 +194,12 @@ def main():
                 "experts_read": n_exp, "expert_gb_per_s": round(gbs, 1),
                 "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
-    base = measure("baseline", spec.top_k, 0.0, args.steps, args.warmup)
     sere = measure("sere", args.S, args.rho, args.steps, args.warmup)
+    if args.only_sere:
+        print(json.dumps({"sere": sere}))
+        return
+    base = measure("baseline", spec.top_k, 0.0, args.steps, args.warmup)
+    run.set_knobs(args.S, args.rho)
     route_us, _, _ = run.time("route", min(args.steps, 200), 10)
 
     # roofline of the dominant kernel: the gate/up projection streams 2/3 of the

@@ -1,26 +1,90 @@
 // Routing kernels: router logits, ordered top-K + gate, and the batch-wide
-// re-routing / compaction kernel.
+// re-routing / compaction step.
 //
 // Paper anchors: router logits R(x) and the top-k gate of the appendix
 // "Preliminaries on MoEs"; primary set, most-similar primary, re-routing
 // condition and final set of Sec. 3.2.2 (Steps 1-3).  The appendix algorithm
 // "CUDA-accelerated SERE" gives one thread to every (token, secondary slot)
 // and lets each scan all M experts; here the scan is done once per secondary
-// EXPERT (its result depends only on the expert and the primary mask), by one
-// 64-lane wavefront, and the rewritten map is counted, prefix-summed and
-// regrouped per expert in the same workgroup, in LDS.
+// EXPERT (its result depends only on the expert and the primary mask), and the
+// rewritten map is counted, prefix-summed and regrouped per expert by the
+// same workgroup, in LDS.
+//
+// Two launches: (1) router logits, (2) top-K per token with one wavefront per
+// token; the workgroup that finishes last (a ticket in global memory, cleared
+// by launch 1) then runs the batch-wide step, so no third launch is needed.
 #pragma once
 
 #include "common.hpp"
 
 namespace sere {
 
+// ------------------------------------------------------------ wave helpers ---
+// Value of lane (l ^ 1), (l ^ 2), mirrored inside 8, mirrored inside 16: four
+// DPP exchanges that together reach every lane of a 16-lane row.
+template <int STEP>
+__device__ __forceinline__ uint32_t row_xchg(uint32_t v) {
+  constexpr int ctrl = STEP == 0 ? 0xB1 : STEP == 1 ? 0x4E : STEP == 2 ? 0x141 : 0x140;
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), ctrl, 0xF, 0xF, true));
+}
+template <int STEP>
+__device__ __forceinline__ double row_xchg(double v) {
+  const uint64_t b = static_cast<uint64_t>(__double_as_longlong(v));
+  const uint64_t r = (static_cast<uint64_t>(row_xchg<STEP>(static_cast<uint32_t>(b >> 32))) << 32) |
+                     row_xchg<STEP>(static_cast<uint32_t>(b));
+  return __longlong_as_double(static_cast<long long>(r));
+}
+
+// sum over the 16 lanes of a row; every lane of the row gets it
+__device__ __forceinline__ double row_sum(double v) {
+  v += row_xchg<0>(v);
+  v += row_xchg<1>(v);
+  v += row_xchg<2>(v);
+  v += row_xchg<3>(v);
+  return v;
+}
+
+// sum over the wavefront (rows through scalar registers); wave-uniform result.
+// The association order is fixed, so equal inputs give bit-equal sums.
+__device__ __forceinline__ double wave_sum_dpp(double v) {
+  v = row_sum(v);
+  const uint64_t b = static_cast<uint64_t>(__double_as_longlong(v));
+  const int lo = static_cast<int>(b), hi = static_cast<int>(b >> 32);
+  double r[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint64_t x = (static_cast<uint64_t>(static_cast<uint32_t>(__builtin_amdgcn_readlane(hi, 16 * q))) << 32) |
+                       static_cast<uint32_t>(__builtin_amdgcn_readlane(lo, 16 * q));
+    r[q] = __longlong_as_double(static_cast<long long>(x));
+  }
+  return (r[0] + r[1]) + (r[2] + r[3]);
+}
+
+// Barrier that orders LDS traffic only: global stores issued earlier (results
+// that nobody in this workgroup reads back) need not have completed.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// order-preserving map double -> uint64 (larger double <=> larger key; -0 == +0)
+__device__ __forceinline__ uint64_t sortable_key(double v) {
+  uint64_t b = static_cast<uint64_t>(__double_as_longlong(v));
+  if (b == 0x8000000000000000ull) b = 0;
+  return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double key_to_double(uint64_t k) {
+  const uint64_t b = (k >> 63) ? (k & 0x7fffffffffffffffull) : ~k;
+  return __longlong_as_double(static_cast<long long>(b));
+}
+
 // ---------------------------------------------------------------------------
 // Router logits in fp64.  grid (ceil(M/16), T), 256 threads; wave w of block
-// (bx, t) computes experts bx*16 + 4w .. +3 for token t.  Every logit is
-// reduced in the same lane pattern, so bit-identical router rows give
-// bit-identical logits (ties then resolve by index, as in exact arithmetic).
-// Block (0,0) also clears the int32 word at `clear_word` (may be NULL).
+// (bx, t) computes experts bx*16 + 4w .. +3 for token t, the four dot products
+// interleaved.  Every logit is reduced in the same lane pattern, so
+// bit-identical router rows give bit-identical logits (ties then resolve by
+// index, as in exact arithmetic).  Block (0,0) clears the int32 at clear_word.
 // ---------------------------------------------------------------------------
 template <int DT>
 __global__ __launch_bounds__(256) void router_logits_kernel(
@@ -30,96 +94,119 @@ __global__ __launch_bounds__(256) void router_logits_kernel(
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (clear_word != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *clear_word = 0;
   const int e0 = blockIdx.x * 16 + wave * 4;
-  for (int q = 0; q < 4; ++q) {
-    const int e = e0 + q;
-    if (e >= M) break;
-    double acc = 0.0;
-    for (int i = lane * 8; i < dh; i += 512) {
-      float xv[8], wv[8];
-      load8<DT>(hidden, static_cast<size_t>(t) * dh + i, xv);
-      load8<DT>(router_w, static_cast<size_t>(e) * dh + i, wv);
+  if (e0 >= M) return;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int i = lane * 8; i < dh; i += 512) {
+    float xv[8];
+    load8<DT>(hidden, static_cast<size_t>(t) * dh + i, xv);
+    double xd[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc = fma(static_cast<double>(xv[j]), static_cast<double>(wv[j]), acc);
+    for (int j = 0; j < 8; ++j) xd[j] = static_cast<double>(xv[j]);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (e0 + q < M) {  // wave-uniform
+        float wv[8];
+        load8<DT>(router_w, static_cast<size_t>(e0 + q) * dh + i, wv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[q] = fma(xd[j], static_cast<double>(wv[j]), acc[q]);
+      }
     }
-    acc = wave_sum(acc);
-    if (lane == 0) logits[static_cast<size_t>(t) * M + e] = acc;
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (e0 + q < M) {
+      const double s = wave_sum_dpp(acc[q]);
+      if (lane == 0) logits[static_cast<size_t>(t) * M + e0 + q] = s;
+    }
   }
 }
 
 // ---------------------------------------------------------------------------
-// Ordered top-K and gate, one wavefront per token (4 tokens per block).
-// K rounds of arg-max over the not-yet-taken logits; a larger logit wins,
-// equal logits go to the lower expert index.  Gate = softmax over the K
-// selected logits (fp64 internally, stored fp32).
+// Ordered top-K and gate.  A 16-lane row of a wavefront owns one token (four
+// tokens per wavefront); lane i of the row holds experts i, i+16, ... (NC per
+// lane, M <= 16*NC).  K rounds of arg-max over the not-yet-taken logits: the
+// larger logit wins, equal logits go to the lower expert index; the row-wide
+// arg-max is four DPP exchanges.  Gate = softmax over the K selected logits
+// (fp64 internally, stored fp32).  `row` is NULL for a row without a token.
+// ids8 (may be NULL) receives the ids as bytes for the workgroup's own use.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void topk_gate_kernel(const double* __restrict__ logits,
-                                                        int32_t* __restrict__ topk_ids,
-                                                        float* __restrict__ topk_w, int T, int M,
-                                                        int K) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int t = blockIdx.x * 4 + wave;
-  if (t >= T) return;  // whole wavefront leaves; the kernel has no barrier
+template <int STEP>
+__device__ __forceinline__ void argmax_step(uint64_t& key, uint32_t& idx) {
+  const uint32_t ohi = row_xchg<STEP>(static_cast<uint32_t>(key >> 32));
+  const uint32_t olo = row_xchg<STEP>(static_cast<uint32_t>(key));
+  const uint32_t oidx = row_xchg<STEP>(idx);
+  const uint64_t okey = (static_cast<uint64_t>(ohi) << 32) | olo;
+  if (okey > key || (okey == key && oidx < idx)) {
+    key = okey;
+    idx = oidx;
+  }
+}
 
-  double cand[4];
-  double mysel[4] = {0.0, 0.0, 0.0, 0.0};  // selected logit of rank k = lane + 64*c
-  double top = 0.0;
-  unsigned taken = 0;
+template <int NC>
+__device__ __forceinline__ void topk_gate_row(const double* __restrict__ row, int32_t* __restrict__ ids,
+                                              float* __restrict__ w, uint8_t* ids8, int M, int K) {
+  const int i = threadIdx.x & 15;
+  uint64_t cand[NC];
+  uint32_t taken = 0;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const int e = lane + 64 * c;
-    if (e < M) {
-      cand[c] = logits[static_cast<size_t>(t) * M + e];
+  for (int c = 0; c < NC; ++c) {
+    const int e = i + 16 * c;
+    if (row != nullptr && e < M) {
+      cand[c] = sortable_key(row[e]);
     } else {
-      cand[c] = 0.0;
+      cand[c] = 0;  // below every real key (0 would be the pattern of a NaN)
       taken |= 1u << c;
     }
   }
+  double mysel[NC];  // selected logit of rank k = i + 16*c
+#pragma unroll
+  for (int c = 0; c < NC; ++c) mysel[c] = 0.0;
+  double top = 0.0;
   for (int k = 0; k < K; ++k) {
-    double bv = -INFINITY;
-    int bi = 0x7fffffff;
+    uint64_t key = 0;
+    uint32_t idx = 0x7fffffffu;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < NC; ++c) {
       const bool ok = !((taken >> c) & 1u);
-      if (ok && (bi == 0x7fffffff || cand[c] > bv)) {
-        bv = cand[c];
-        bi = lane + 64 * c;
+      if (ok && (idx == 0x7fffffffu || cand[c] > key)) {  // strict '>' keeps the lower index
+        key = cand[c];
+        idx = i + 16 * c;
       }
     }
+    argmax_step<0>(key, idx);
+    argmax_step<1>(key, idx);
+    argmax_step<2>(key, idx);
+    argmax_step<3>(key, idx);
+    // every lane of the row now holds the winner
+    const double val = key_to_double(key);
+    if ((idx & 15u) == static_cast<uint32_t>(i)) taken |= 1u << (idx >> 4);
+    if (k == 0) top = val;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      const double ov = __shfl_xor(bv, off, kWave);
-      const int oi = __shfl_xor(bi, off, kWave);
-      const bool mine_valid = bi != 0x7fffffff, other_valid = oi != 0x7fffffff;
-      const bool take = other_valid && (!mine_valid || ov > bv || (ov == bv && oi < bi));
-      if (take) {
-        bv = ov;
-        bi = oi;
-      }
+    for (int c = 0; c < NC; ++c)
+      if (k == i + 16 * c) mysel[c] = val;
+    if (i == 0 && row != nullptr) {
+      ids[k] = static_cast<int32_t>(idx);
+      if (ids8 != nullptr) ids8[k] = static_cast<uint8_t>(idx);
     }
-    // every lane now holds the winner (bv, bi)
-    if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-    if (k == 0) top = bv;
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-      if (k == lane + 64 * c) mysel[c] = bv;
-    if (lane == 0) topk_ids[static_cast<size_t>(t) * K + k] = bi;
   }
-  double ex[4];
+  double ex[NC];
   double part = 0.0;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    ex[c] = (lane + 64 * c < K) ? exp(mysel[c] - top) : 0.0;
-    part += ex[c];
+  for (int c = 0; c < NC; ++c) {
+    ex[c] = 0.0;
+    if (16 * c < K) {  // uniform
+      ex[c] = (i + 16 * c < K) ? exp(mysel[c] - top) : 0.0;
+      part += ex[c];
+    }
   }
-  const double denom = wave_sum(part);
+  const double denom = row_sum(part);
 #pragma unroll
-  for (int c = 0; c < 4; ++c)
-    if (lane + 64 * c < K)
-      topk_w[static_cast<size_t>(t) * K + lane + 64 * c] = static_cast<float>(ex[c] / denom);
+  for (int c = 0; c < NC; ++c)
+    if (i + 16 * c < K && row != nullptr) w[i + 16 * c] = static_cast<float>(ex[c] / denom);
 }
 
 // ---------------------------------------------------------------------------
-// Batch-wide re-routing and compaction: ONE workgroup of 1024 threads.
+// Batch-wide re-routing and compaction by ONE workgroup of 1024 threads.
 // ---------------------------------------------------------------------------
 struct RouteArgs {
   const int32_t* topk_ids;  // [A]  I
@@ -144,111 +231,176 @@ struct RouteArgs {
 
 constexpr int kRouteThreads = 1024;
 constexpr int kRouteWaves = kRouteThreads / kWave;
+constexpr int kTokensPerBlock = 4 * kRouteWaves;  // one 16-lane row per token
+constexpr int kIdsInLds = 4096;                   // slots whose ids a lone workgroup keeps in LDS
 
-__global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs p) {
-  __shared__ int s_cnt_b[SERE_MAX_EXPERTS];
-  __shared__ int s_cnt_a[SERE_MAX_EXPERTS];
-  __shared__ int s_prim[SERE_MAX_EXPERTS];
-  __shared__ int s_remap[SERE_MAX_EXPERTS];
-  __shared__ int s_scan_cnt[SERE_MAX_EXPERTS];
-  __shared__ int s_scan_act[SERE_MAX_EXPERTS];
-  __shared__ int s_cursor[SERE_MAX_EXPERTS];
-  __shared__ int s_round[kRouteWaves][SERE_MAX_EXPERTS];
+struct RouteShared {
+  int cnt_b[SERE_MAX_EXPERTS];
+  int cnt_a[SERE_MAX_EXPERTS];
+  int prim[SERE_MAX_EXPERTS];
+  int remap[SERE_MAX_EXPERTS];
+  int scan_cnt[SERE_MAX_EXPERTS / kWave];
+  int scan_act[SERE_MAX_EXPERTS / kWave];
+  int scan_before[SERE_MAX_EXPERTS / kWave];
+  int cursor[SERE_MAX_EXPERTS];
+  int round_cnt[kRouteWaves][SERE_MAX_EXPERTS];
+  uint8_t ids8[kIdsInLds];
+  int flag;
+};
 
+// Rows of sim are scanned by 16-lane rows of a wavefront: row group q = lane/16
+// of wavefront w owns experts u = 4*w + q + 64*r (r = 0, 1, ...); lane i of the
+// group reads sim[u][i], sim[u][i + 16], ...: a load instruction touches four
+// 64-byte segments, and the arg-max of a row needs only the four in-row DPP
+// exchanges.  NC (4, 8 or 16) bounds M <= 16*NC.  The first values of a lane
+// are loaded up front, before it is known which experts are secondary at all,
+// so that their latency hides behind the top-K.
+template <int NC>
+struct SimPrefetch {
+  static constexpr int NR = NC / 4;              // rounds of 64 experts
+  static constexpr int PR = NC == 16 ? 1 : NR;   // rounds fetched ahead (at most 16 values per lane)
+  float v[PR * NC];
+};
+template <int NC>
+__device__ __forceinline__ void prefetch_sim(const RouteArgs& p, SimPrefetch<NC>& pf) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int q = lane >> 4, i = lane & 15;
+#pragma unroll
+  for (int r = 0; r < SimPrefetch<NC>::PR; ++r) {
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      const int u = 4 * wave + q + 64 * r, v = i + 16 * c;
+      pf.v[r * NC + c] = (p.reroute && u < p.M && v < p.M) ? p.sim[static_cast<size_t>(u) * p.M + v] : 0.0f;
+    }
+  }
+}
+
+// arg-max step over (similarity, index): larger similarity wins, equal goes to the lower index
+template <int STEP>
+__device__ __forceinline__ void simmax_step(float& sv, int& iv) {
+  const float os = __uint_as_float(row_xchg<STEP>(__float_as_uint(sv)));
+  const int oi = static_cast<int>(row_xchg<STEP>(static_cast<uint32_t>(iv)));
+  if (os > sv || (os == sv && oi < iv)) {
+    sv = os;
+    iv = oi;
+  }
+}
+
+template <bool IDS_IN_LDS, int NC>
+__device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, const SimPrefetch<NC>& pf) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int M = p.M, K = p.K, S = p.S;
   const int A = p.T * K;
+  auto id_at = [&](int a) -> int { return IDS_IN_LDS ? static_cast<int>(s.ids8[a]) : p.topk_ids[a]; };
 
   if (tid < SERE_MAX_EXPERTS) {
-    s_cnt_b[tid] = 0;
-    s_cnt_a[tid] = 0;
-    s_prim[tid] = 0;
-    s_remap[tid] = tid;
+    s.cnt_b[tid] = 0;
+    s.cnt_a[tid] = 0;
+    s.prim[tid] = 0;
+    s.remap[tid] = tid;
   }
-  for (int i = tid; i < kRouteWaves * SERE_MAX_EXPERTS; i += kRouteThreads) (&s_round[0][0])[i] = 0;
-  __syncthreads();
+  for (int i = tid; i < kRouteWaves * SERE_MAX_EXPERTS; i += kRouteThreads) (&s.round_cnt[0][0])[i] = 0;
+  lds_barrier();
 
   // Step 1: activation histogram and primary mask (union of every token's top-S)
   for (int a = tid; a < A; a += kRouteThreads) {
-    const int e = p.topk_ids[a];
-    atomicAdd(&s_cnt_b[e], 1);
-    if (a % K < S) s_prim[e] = 1;
+    const int e = id_at(a);
+    atomicAdd(&s.cnt_b[e], 1);
+    if (a % K < S) s.prim[e] = 1;
   }
-  __syncthreads();
+  lds_barrier();
 
   // Step 2: per secondary expert u (activated, not primary): most similar
-  // primary v*, ascending scan with strict '>' (lowest index wins a tie, start
-  // value (-inf, expert 0)); kept as critical iff rho > 0 and sim* < rho.
+  // primary v*.  Each lane keeps the first maximum of its own columns in
+  // ascending order with strict '>' (start value (-inf, expert 0)); lanes are
+  // merged preferring the larger similarity, then the lower index: together
+  // the first maximum of an ascending scan, as the paper's algorithm finds it.
+  // The expert is kept as critical iff rho > 0 and sim* < rho.
   if (p.reroute) {
-    for (int u = wave; u < M; u += kRouteWaves) {
-      if (s_cnt_b[u] == 0 || s_prim[u]) continue;  // wave-uniform
+    const int q = lane >> 4, i = lane & 15;
+#pragma unroll
+    for (int r = 0; r < SimPrefetch<NC>::NR; ++r) {
+      const int u = 4 * wave + q + 64 * r;
+      const bool sec = u < M && s.cnt_b[u] > 0 && !s.prim[u];
+      if (__ballot(sec) == 0) continue;  // wave-uniform
       float bs = -INFINITY;
       int bv = 0;
-      for (int v = lane; v < M; v += kWave) {
-        if (s_prim[v]) {
-          const float s = p.sim[static_cast<size_t>(u) * M + v];
-          if (s > bs) {
-            bs = s;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int v = i + 16 * c;
+        if (v < M) {
+          float sv;
+          if (r < SimPrefetch<NC>::PR)
+            sv = pf.v[(r < SimPrefetch<NC>::PR ? r : 0) * NC + c];
+          else
+            sv = sec ? p.sim[static_cast<size_t>(u) * M + v] : 0.0f;
+          if (s.prim[v] && sv > bs) {
+            bs = sv;
             bv = v;
           }
         }
       }
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) {
-        const float os = __shfl_xor(bs, off, kWave);
-        const int ov = __shfl_xor(bv, off, kWave);
-        if (os > bs || (os == bs && ov < bv)) {
-          bs = os;
-          bv = ov;
-        }
-      }
-      if (lane == 0) s_remap[u] = (p.rho > 0.0f && bs < p.rho) ? u : bv;
+      simmax_step<0>(bs, bv);
+      simmax_step<1>(bs, bv);
+      simmax_step<2>(bs, bv);
+      simmax_step<3>(bs, bv);
+      if (sec && i == 0) s.remap[u] = (p.rho > 0.0f && bs < p.rho) ? u : bv;
     }
   }
-  __syncthreads();
+  lds_barrier();
 
   // Step 3: rewrite secondary slots, count the new map
   for (int a = tid; a < A; a += kRouteThreads) {
-    const int e = p.topk_ids[a];
-    const int e2 = (a % K >= S) ? s_remap[e] : e;
+    const int e = id_at(a);
+    const int e2 = (a % K >= S) ? s.remap[e] : e;
     p.rerouted_ids[a] = e2;
-    atomicAdd(&s_cnt_a[e2], 1);
+    atomicAdd(&s.cnt_a[e2], 1);
   }
-  __syncthreads();
+  lds_barrier();
 
-  // inclusive scans over experts: slots (-> offsets) and activity (-> work list rank)
+  // inclusive scans over experts: slots (-> offsets) and activity (-> work list
+  // rank); inside each of the first four wavefronts by shuffles, across them
+  // through four totals in LDS
   const bool is_e = tid < SERE_MAX_EXPERTS;
-  const int my_cnt = (is_e && tid < M) ? s_cnt_a[tid] : 0;
+  const int my_cnt = (is_e && tid < M) ? s.cnt_a[tid] : 0;
   const int my_act = my_cnt > 0 ? 1 : 0;
-  const int n_before = __syncthreads_count(is_e && tid < M && s_cnt_b[tid] > 0);
-  if (is_e) {
-    s_scan_cnt[tid] = my_cnt;
-    s_scan_act[tid] = my_act;
-  }
-  __syncthreads();
-  for (int d = 1; d < SERE_MAX_EXPERTS; d <<= 1) {
-    int add_c = 0, add_a = 0;
-    if (is_e && tid >= d) {
-      add_c = s_scan_cnt[tid - d];
-      add_a = s_scan_act[tid - d];
+  int inc_cnt = my_cnt, inc_act = my_act;
+  if (is_e) {  // wave-uniform (waves 0-3)
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int uc = __shfl_up(inc_cnt, d, kWave), ua = __shfl_up(inc_act, d, kWave);
+      if (lane >= d) {
+        inc_cnt += uc;
+        inc_act += ua;
+      }
     }
-    __syncthreads();
-    if (is_e) {
-      s_scan_cnt[tid] += add_c;
-      s_scan_act[tid] += add_a;
+    if (lane == kWave - 1) {
+      s.scan_cnt[wave] = inc_cnt;
+      s.scan_act[wave] = inc_act;
     }
-    __syncthreads();
+    const int nb = __popcll(__ballot(tid < M && s.cnt_b[tid] > 0));
+    if (lane == 0) s.scan_before[wave] = nb;
   }
-  const int n_after = s_scan_act[SERE_MAX_EXPERTS - 1];
+  lds_barrier();
+  int n_after = 0, n_before = 0;
+#pragma unroll
+  for (int w = 0; w < SERE_MAX_EXPERTS / kWave; ++w) {
+    if (is_e && w < wave) {
+      inc_cnt += s.scan_cnt[w];
+      inc_act += s.scan_act[w];
+    }
+    n_after += s.scan_act[w];
+    n_before += s.scan_before[w];
+  }
   if (is_e && tid < M) {
-    const int off = s_scan_cnt[tid] - my_cnt;
-    s_cursor[tid] = off;
+    const int off = inc_cnt - my_cnt;
+    s.cursor[tid] = off;
     p.expert_offsets[tid] = off;
-    p.count_before[tid] = s_cnt_b[tid];
+    p.count_before[tid] = s.cnt_b[tid];
     p.count_after[tid] = my_cnt;
-    p.primary_mask[tid] = s_prim[tid];
+    p.primary_mask[tid] = s.prim[tid];
     if (my_act) {
-      const int i = s_scan_act[tid] - 1;
+      const int i = inc_act - 1;
       p.work_expert[i] = tid;
       p.work_off[i] = off;
       p.work_cnt[i] = my_cnt;
@@ -266,47 +418,103 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs p) {
     p.work_cnt[n_after + tid] = p.T;
   }
   for (int i = tid; i < p.n_sh * p.T; i += kRouteThreads) p.sorted_token[A + i] = i % p.T;
-  __syncthreads();
+  lds_barrier();
 
   // Stable regrouping by expert: slots keep ascending (token, slot) order
   // inside each expert.  A round covers 1024 consecutive slots, one wavefront
-  // per 64; rank inside the wavefront by comparing against every lane, rank
-  // across wavefronts through the per-round table.
+  // per 64; rank inside the wavefront from ballots, rank across wavefronts
+  // through the per-round table.
   for (int base = 0; base < A; base += kRouteThreads) {
     const int a = base + tid;
     const bool valid = a < A;
-    int e = -1;
+    int e = 0;
     if (valid) {
-      const int e0 = p.topk_ids[a];
-      e = (a % K >= S) ? s_remap[e0] : e0;
+      const int e0 = id_at(a);
+      e = (a % K >= S) ? s.remap[e0] : e0;
     }
+    // lanes of this wavefront holding the same expert: intersect, over the 8
+    // bits of e, the ballot of lanes that agree with this lane on that bit
     int rank = 0, same = 0;
-    for (int j = 0; j < kWave; ++j) {
-      const int ej = __builtin_amdgcn_readlane(e, j);
-      const int eq = (ej == e) ? 1 : 0;
-      same += eq;
-      rank += (j < lane) ? eq : 0;
+    if (base + wave * kWave < A) {  // wave-uniform: this wavefront has slots
+      uint64_t peers = __ballot(valid);
+#pragma unroll
+      for (int bit = 0; bit < 8; ++bit) {
+        const bool set = (e >> bit) & 1;
+        const uint64_t with = __ballot(set);
+        peers &= set ? with : ~with;
+      }
+      same = __popcll(peers);
+      rank = __popcll(peers & ((1ull << lane) - 1ull));
     }
-    if (valid && rank == 0) s_round[wave][e] = same;
-    __syncthreads();
+    if (valid && rank == 0) s.round_cnt[wave][e] = same;
+    lds_barrier();
     if (valid) {
-      int pos = s_cursor[e] + rank;
-      for (int w = 0; w < wave; ++w) pos += s_round[w][e];
+      int pos = s.cursor[e] + rank;
+      for (int w = 0; w < wave; ++w) pos += s.round_cnt[w][e];
       p.sorted_token[pos] = a / K;
       p.sorted_slot[pos] = a % K;
       p.slot_pos[a] = pos;
     }
-    __syncthreads();
-    if (is_e && tid < M) {
-      int add = 0;
-      for (int w = 0; w < kRouteWaves; ++w) {
-        add += s_round[w][tid];
-        s_round[w][tid] = 0;
+    if (base + kRouteThreads < A) {  // another round follows: advance the cursors
+      lds_barrier();
+      if (is_e && tid < M) {
+        int add = 0;
+        for (int w = 0; w < kRouteWaves; ++w) {
+          add += s.round_cnt[w][tid];
+          s.round_cnt[w][tid] = 0;
+        }
+        s.cursor[tid] += add;
       }
-      s_cursor[tid] += add;
+      lds_barrier();
     }
+  }
+}
+
+// Re-routing alone (indices in, indices out): grid 1, 1024 threads.
+__global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs p) {
+  __shared__ RouteShared s;
+  SimPrefetch<16> pf;  // any M up to 256
+  prefetch_sim(p, pf);
+  route_phase<false>(p, s, pf);
+}
+
+// Top-K + gate (64 tokens per workgroup), then the batch-wide step by the
+// workgroup that takes the last ticket.  With a single workgroup (T <= 64)
+// there is no ticket and the ids go from the top-K to the batch-wide step
+// through LDS.  grid ceil(T/64), 1024 threads; *ticket must be 0 at launch.
+// NC = ceil(M / 16) rounded up to 4, 8 or 16.
+template <int NC>
+__global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const double* __restrict__ logits,
+                                                                   int32_t* __restrict__ topk_ids,
+                                                                   float* __restrict__ topk_w, int32_t* ticket,
+                                                                   RouteArgs p) {
+  __shared__ RouteShared s;
+  SimPrefetch<NC> pf;
+  prefetch_sim(p, pf);
+  const int t = blockIdx.x * kTokensPerBlock + (threadIdx.x >> 4);
+  const bool lone = gridDim.x == 1 && p.T * p.K <= kIdsInLds;
+  const bool has = t < p.T;
+  if (blockIdx.x * kTokensPerBlock + 4 * (threadIdx.x >> 6) < p.T)  // wave-uniform: the wavefront has a token
+    topk_gate_row<NC>(has ? logits + static_cast<size_t>(t) * p.M : nullptr,
+                      topk_ids + static_cast<size_t>(has ? t : 0) * p.K,
+                      topk_w + static_cast<size_t>(has ? t : 0) * p.K,
+                      lone ? s.ids8 + static_cast<size_t>(has ? t : 0) * p.K : nullptr, p.M, p.K);
+  if (lone) {
+    __syncthreads();
+    route_phase<true>(p, s, pf);
+    return;
+  }
+  if (gridDim.x > 1) {
+    __threadfence();  // this workgroup's top-K results are visible device-wide ...
+    __syncthreads();
+    if (threadIdx.x == 0) s.flag = atomicAdd(ticket, 1) == static_cast<int>(gridDim.x) - 1;
+    __syncthreads();
+    if (!s.flag) return;  // ... before the last workgroup reads them
+    __threadfence();
+  } else {
     __syncthreads();
   }
+  route_phase<false>(p, s, pf);
 }
 
 }  // namespace sere

@@ -16,7 +16,7 @@ namespace sere {
 // ---------------------------------------------------------------- layout ---
 struct Layout {
   size_t logits, topk_ids, topk_w, rerouted, cnt_before, cnt_after, primary, num_active, offsets,
-      sorted_token, sorted_slot, slot_pos, work_expert, work_off, work_cnt, n_work, h, y, total;
+      sorted_token, sorted_slot, slot_pos, work_expert, work_off, work_cnt, n_work, ticket, h, y, total;
   int rows;    // A + n_sh*T rows of the sorted slot list
   int ksplit;  // slices of d_m in the down projection
 };
@@ -58,6 +58,7 @@ static Layout make_layout(const sere_config& c) {
   l.work_off = take(W * 4);
   l.work_cnt = take(W * 4);
   l.n_work = take(4);
+  l.ticket = take(4);
   l.h = take(R * c.inter * sizeof(float));
   l.y = take(static_cast<size_t>(l.ksplit) * R * c.hidden * sizeof(float));
   l.total = o;
@@ -158,6 +159,7 @@ struct StageTimer {
 // --------------------------------------------------------------- launches ---
 struct Pointers {
   double* logits;
+  int32_t* ticket;
   int32_t* topk_ids;
   float* topk_w;
   RouteArgs route;
@@ -172,6 +174,7 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
   if (o == nullptr) o = &none;
   Pointers p{};
   p.logits = reinterpret_cast<double*>(ws + l.logits);
+  p.ticket = reinterpret_cast<int32_t*>(ws + l.ticket);
   p.topk_ids = static_cast<int32_t*>(pick(o->topk_ids, l.topk_ids));
   p.topk_w = static_cast<float*>(pick(o->topk_weights, l.topk_w));
   RouteArgs& r = p.route;
@@ -209,10 +212,10 @@ static int launch_router(const sere_config& c, const Pointers& p, const void* hi
     dim3 grid((c.num_experts + 15) / 16, c.num_tokens);
     if (c.dtype == SERE_F32)
       hipLaunchKernelGGL(router_logits_kernel<SERE_F32>, grid, dim3(256), 0, s, hidden, router_w, p.logits,
-                         c.num_tokens, c.num_experts, c.hidden, static_cast<int32_t*>(nullptr));
+                         c.num_tokens, c.num_experts, c.hidden, p.ticket);
     else
       hipLaunchKernelGGL(router_logits_kernel<SERE_BF16>, grid, dim3(256), 0, s, hidden, router_w, p.logits,
-                         c.num_tokens, c.num_experts, c.hidden, static_cast<int32_t*>(nullptr));
+                         c.num_tokens, c.num_experts, c.hidden, p.ticket);
   }
   return hip_status();
 }
@@ -221,10 +224,19 @@ static int launch_route(const sere_config& c, const Pointers& p, bool with_topk,
                         const sere_route_out* o, size_t sorted_token_bytes) {
   {
     StageTimer tm(SERE_STAGE_ROUTE, s);
-    if (with_topk)
-      hipLaunchKernelGGL(topk_gate_kernel, dim3((c.num_tokens + 3) / 4), dim3(256), 0, s, p.logits, p.topk_ids,
-                         p.topk_w, c.num_tokens, c.num_experts, c.top_k);
-    hipLaunchKernelGGL(route_kernel, dim3(1), dim3(kRouteThreads), 0, s, p.route);
+    if (with_topk) {
+      const dim3 grid((c.num_tokens + kTokensPerBlock - 1) / kTokensPerBlock);
+      if (c.num_experts <= 64)
+        hipLaunchKernelGGL(topk_route_kernel<4>, grid, dim3(kRouteThreads), 0, s, p.logits, p.topk_ids, p.topk_w,
+                           p.ticket, p.route);
+      else if (c.num_experts <= 128)
+        hipLaunchKernelGGL(topk_route_kernel<8>, grid, dim3(kRouteThreads), 0, s, p.logits, p.topk_ids, p.topk_w,
+                           p.ticket, p.route);
+      else
+        hipLaunchKernelGGL(topk_route_kernel<16>, grid, dim3(kRouteThreads), 0, s, p.logits, p.topk_ids, p.topk_w,
+                           p.ticket, p.route);
+    } else
+      hipLaunchKernelGGL(route_kernel, dim3(1), dim3(kRouteThreads), 0, s, p.route);
     // the internal sorted_token list also carries the shared experts' rows; a
     // caller-visible copy holds the routed part only
     if (o != nullptr && o->sorted_token != nullptr)
