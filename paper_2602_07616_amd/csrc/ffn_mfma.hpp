@@ -73,116 +73,164 @@ constexpr int kGateUpJ = 8;    // intermediate indices per wavefront (8 gate row
 constexpr int kDownRows = 32;  // output rows per wavefront (two tiles)
 constexpr int kWavesPerBlock = 4;
 
-// The token operand is loaded the same way: half tile BX = tokens 0-7 of the
-// tile, BY = tokens 8-15, lane (g, i) -> token (i & 7), chunk 2g + (i >> 3), so a
-// load instruction again covers whole lines (8 tokens x 128 B); BY is skipped
-// when the tile has at most 8 tokens.
-struct TokenRows {
-  const uint16_t* x;  // lane's address in half tile BX at k = 0, or NULL
-  const uint16_t* y;  // same for BY
+// The token operand (hidden states for gate/up, h for down) is shared by the
+// four wavefronts of a workgroup and staged through LDS in k chunks, double
+// buffered: 256 threads copy a chunk of all token rows with 128-bit loads while
+// the previous chunk is being multiplied; lane (g, n) then reads its MFMA
+// operand straight from LDS (row n, k offset 16g: chunk 2g for A_even, 2g+1
+// for A_odd).  A row of the LDS tile is padded by 16 bytes so that the 16 lanes
+// of a 128-bit read fall into 16 different bank groups.
+
+// geometry of one staging configuration
+template <int NT, int KC>
+struct Stage {
+  static constexpr int kRows = NT * kTile;           // token rows held
+  static constexpr int kRowBytes = KC * 2 + 16;      // padded LDS row
+  static constexpr int kBufBytes = kRows * kRowBytes;
+  static constexpr int kPiecesPerRow = KC / 8;       // 16-byte pieces
+  static constexpr int kPerThread = kRows * kPiecesPerRow / 256;
+  static_assert(kPerThread >= 1 && kRows * kPiecesPerRow % 256 == 0, "chunk must split over 256 threads");
+};
+constexpr int kStageLdsBytes = 2 * Stage<4, 128>::kBufBytes;  // the largest configuration, two buffers
+
+// Token rows of a group: row r (< nrows) of the group is row index[first + r]
+// (or first + r if index is NULL) of a matrix with leading dimension ld.
+struct TokenSource {
+  const uint16_t* base;
+  const int32_t* index;
+  int first, nrows, ld;
 };
 
-// acc[a][t] += W_tile_a[16 x (kend-kbeg)] * tokens_t, for NA weight tiles that
-// share the token operand and NT token tiles.
+// acc[a][t] += W_tile_a[16 x (kend-kbeg)] * tokens_t, for NA weight tiles and
+// NT token tiles.
 //   wx[a], wy[a] : this lane's address in half tile X / Y of weight tile a at k = 0
 //                  (row (i&7), chunk 2g + (i>>3))
+//   rot          : chunk the workgroup starts with (the chunks are visited cyclically), so
+//                  that concurrently running workgroups do not all hit the same offset
+//                  inside their rows (and thus the same HBM channels)
 //   lo_plane     : with LO, a second token operand `lo_plane` elements after the
 //                  first is multiplied too (token = high + low bf16 parts)
-//   rot          : multiple of 64 below kend-kbeg; the 64-wide k blocks are visited
-//                  starting there and wrapping around, so that concurrently running
-//                  wavefronts do not all hit the same offset inside their rows
-template <int NA, int NT, int U, bool LO>
-__device__ __forceinline__ void stream_tile(const uint16_t* const (&wx)[NA], const uint16_t* const (&wy)[NA],
-                                            const TokenRows (&b)[NT], const bool (&need_y)[NT], size_t lo_plane,
-                                            int kbeg, int kend, int rot, f32x4 (&acc)[NA][NT]) {
+// All 256 threads of the workgroup must call this together (it has barriers).
+template <int NA, int NT, int KC, bool LO>
+__device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], const uint16_t* const (&wy)[NA],
+                                             const TokenSource& tok, size_t lo_plane, int kbeg, int kend, int rot,
+                                             unsigned char* lds, f32x4 (&acc)[NA][NT]) {
+  using St = Stage<NT, KC>;
+  constexpr int KB = KC / 64;          // 64-wide k blocks per chunk
+  constexpr int H0 = (KB + 1) / 2;     // k blocks in the first half of a chunk
+  constexpr int NP = LO ? 2 : 1;
+  static_assert(NP * 2 * St::kBufBytes <= kStageLdsBytes, "LDS budget");
   const u32x4 zero = {0u, 0u, 0u, 0u};
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int i = lane & 15, g = lane >> 4;
   const int len = kend - kbeg;
-  constexpr int NP = LO ? 2 : 1;  // planes of the token operand (high [, low])
-  for (int k0 = 0; k0 < len; k0 += 64 * U) {
-    u32x4 x[NA][U], y[NA][U], bx[NP][NT][U], by[NP][NT][U];
+  const int nch = (len + KC - 1) / KC;
+
+  // this thread's pieces of a chunk: (row, 16-byte column) pairs, the same for every chunk
+  const uint16_t* src[St::kPerThread];
+  int dst[St::kPerThread], col[St::kPerThread];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int off = k0 + 64 * u;
-      if (off < len) {  // wave-uniform
-        int kk = off + rot;
-        if (kk >= len) kk -= len;
-        kk += kbeg;
+  for (int j = 0; j < St::kPerThread; ++j) {
+    const int pc = tid + 256 * j;
+    const int row = pc / St::kPiecesPerRow;
+    col[j] = (pc % St::kPiecesPerRow) * 8;
+    dst[j] = row * St::kRowBytes + col[j] * 2;
+    src[j] = row < tok.nrows
+                 ? tok.base + static_cast<size_t>(tok.index != nullptr ? tok.index[tok.first + row] : tok.first + row) * tok.ld
+                 : nullptr;
+  }
+  auto chunk_start = [&](int c) {
+    int cc = c + rot;
+    if (cc >= nch) cc -= nch;
+    return kbeg + cc * KC;
+  };
+  u32x4 stage[NP][St::kPerThread];
+  auto fetch_tokens = [&](int k0) {
 #pragma unroll
-        for (int a = 0; a < NA; ++a) {
-          x[a][u] = load_weight(wx[a] + kk);
-          y[a][u] = load_weight(wy[a] + kk);
-        }
+    for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-        for (int pl = 0; pl < NP; ++pl) {
+      for (int j = 0; j < St::kPerThread; ++j)
+        stage[pl][j] = (src[j] != nullptr && k0 + col[j] < kend) ? load_reused(src[j] + pl * lo_plane + k0 + col[j]) : zero;
+  };
+  auto store_tokens = [&](int buf) {
 #pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            bx[pl][t][u] = b[t].x != nullptr ? load_reused(b[t].x + pl * lo_plane + kk) : zero;
-            by[pl][t][u] = (need_y[t] && b[t].y != nullptr) ? load_reused(b[t].y + pl * lo_plane + kk) : zero;
-          }
-        }
-      } else {
+    for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-        for (int a = 0; a < NA; ++a) x[a][u] = y[a][u] = zero;
+      for (int j = 0; j < St::kPerThread; ++j)
+        *reinterpret_cast<u32x4*>(lds + (buf * NP + pl) * St::kBufBytes + dst[j]) = stage[pl][j];
+  };
+  // weights of one half of a chunk: k blocks [b0, b1)
+  u32x4 xa[NA][H0], ya[NA][H0], xb[NA][H0], yb[NA][H0];
+  auto fetch_weights = [&](u32x4 (&x)[NA][H0], u32x4 (&y)[NA][H0], int k0, int b0, int b1) {
 #pragma unroll
-        for (int pl = 0; pl < NP; ++pl) {
-#pragma unroll
-          for (int t = 0; t < NT; ++t) bx[pl][t][u] = by[pl][t][u] = zero;
-        }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      u32x4 b_even[NP][NT], b_odd[NP][NT];
-#pragma unroll
-      for (int pl = 0; pl < NP; ++pl) {
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          b_even[pl][t] = upper_from(bx[pl][t][u], by[pl][t][u]);
-          b_odd[pl][t] = lower_from(by[pl][t][u], bx[pl][t][u]);
-        }
-      }
+    for (int b = b0; b < b1; ++b) {
+      const int kk = k0 + 64 * b;
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
-        const u32x4 a_even = upper_from(x[a][u], y[a][u]);
-        const u32x4 a_odd = lower_from(y[a][u], x[a][u]);
+        x[a][b - b0] = kk < kend ? load_weight(wx[a] + kk) : zero;  // wave-uniform condition
+        y[a][b - b0] = kk < kend ? load_weight(wy[a] + kk) : zero;
+      }
+    }
+  };
+  auto multiply = [&](const u32x4 (&x)[NA][H0], const u32x4 (&y)[NA][H0], int k0, int b0, int b1, int buf) {
 #pragma unroll
-        for (int pl = 0; pl < NP; ++pl) {
+    for (int b = b0; b < b1; ++b) {
+      if (k0 + 64 * b < kend) {  // wave-uniform; skipped blocks hold no valid token data either
+        u32x4 b_even[NP][NT], b_odd[NP][NT];
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
           for (int t = 0; t < NT; ++t) {
-            acc[a][t] = mfma_bf16(a_even, b_even[pl][t], acc[a][t]);
-            acc[a][t] = mfma_bf16(a_odd, b_odd[pl][t], acc[a][t]);
+            const unsigned char* at =
+                lds + (buf * NP + pl) * St::kBufBytes + (t * kTile + i) * St::kRowBytes + (64 * b + 16 * g) * 2;
+            b_even[pl][t] = *reinterpret_cast<const u32x4*>(at);
+            b_odd[pl][t] = *reinterpret_cast<const u32x4*>(at + 16);
           }
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+          const u32x4 a_even = upper_from(x[a][b - b0], y[a][b - b0]);
+          const u32x4 a_odd = lower_from(y[a][b - b0], x[a][b - b0]);
+#pragma unroll
+          for (int pl = 0; pl < NP; ++pl)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+              acc[a][t] = mfma_bf16(a_even, b_even[pl][t], acc[a][t]);
+              acc[a][t] = mfma_bf16(a_odd, b_odd[pl][t], acc[a][t]);
+            }
         }
       }
     }
+  };
+
+  if (nch > 0) {
+    int k0 = chunk_start(0);
+    fetch_tokens(k0);
+    fetch_weights(xa, ya, k0, 0, H0);
+    if (KB > H0) fetch_weights(xb, yb, k0, H0, KB);
+    store_tokens(0);
+    for (int c = 0; c < nch; ++c) {
+      __syncthreads();  // chunk c is in LDS; nobody still reads the other buffer
+      const int k1 = c + 1 < nch ? chunk_start(c + 1) : kend;  // kend: nothing left to fetch
+      if (c + 1 < nch) fetch_tokens(k1);
+      multiply(xa, ya, k0, 0, H0, c & 1);
+      if (c + 1 < nch) fetch_weights(xa, ya, k1, 0, H0);
+      if (KB > H0) {
+        multiply(xb, yb, k0, H0, KB, c & 1);
+        if (c + 1 < nch) fetch_weights(xb, yb, k1, H0, KB);
+      }
+      if (c + 1 < nch) store_tokens((c + 1) & 1);
+      k0 = k1;
+    }
   }
+  __syncthreads();  // the LDS buffers may be refilled by the caller's next group
 }
 
-// rows of the token operand for NT tiles starting at `first`; `nrows` valid rows, row stride `ld`
-template <int NT>
-__device__ __forceinline__ void token_rows(const uint16_t* base, const int32_t* index, int first, int nrows,
-                                           int ld, TokenRows (&b)[NT], bool (&need_y)[NT]) {
-  const int lane = threadIdx.x & 63;
-  const int i = lane & 15, g = lane >> 4;
-  const int chunk = 2 * g + (i >> 3);
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int nx = t * kTile + (i & 7), ny = nx + 8;
-    const int rx = nx < nrows ? (index != nullptr ? index[first + nx] : first + nx) : -1;
-    const int ry = ny < nrows ? (index != nullptr ? index[first + ny] : first + ny) : -1;
-    b[t].x = rx >= 0 ? base + static_cast<size_t>(rx) * ld + 8 * chunk : nullptr;
-    b[t].y = ry >= 0 ? base + static_cast<size_t>(ry) * ld + 8 * chunk : nullptr;
-    need_y[t] = nrows > t * kTile + 8;  // wave-uniform
-  }
-}
-
-// starting k block of a wavefront: spread over the row so that the chip's
-// wavefronts touch different offsets (and thus HBM channels) at any moment
-__device__ __forceinline__ int start_rotation(int len) {
-  const int n = len >> 6;
+// first chunk of a workgroup: spread over the row
+__device__ __forceinline__ int start_rotation(int len, int chunk) {
+  const int n = (len + chunk - 1) / chunk;
   if (n <= 1) return 0;
-  const unsigned id = (blockIdx.y * gridDim.x + blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
-  return static_cast<int>((id * 5u) % static_cast<unsigned>(n)) << 6;
+  const unsigned id = blockIdx.y * gridDim.x + blockIdx.x;
+  return static_cast<int>((id * 5u) % static_cast<unsigned>(n));
 }
 
 // ---------------------------------------------------------------------------
@@ -191,25 +239,22 @@ __device__ __forceinline__ int start_rotation(int len) {
 // X), rows 8-15 = the matching up rows (half tile Y).  Lanes with g < 2 end
 // with gate values, lanes g + 2 with the up values of the same (j, token);
 // h = silu(gate) * up is stored as bf16 (plus, if split_h, the bf16 rounding
-// residual in a second plane).  (Measured against a variant with a
-// 16-row gate tile and a 16-row up tile per wavefront: this one keeps twice
-// as many wavefronts in flight and is faster when few experts survive.)
+// residual in a second plane).
 // ---------------------------------------------------------------------------
-template <int NT, int U>
-__device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W, int j0, int row0, int nrows) {
+template <int NT, int KC>
+__device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W, int j0, int row0, int nrows,
+                                             unsigned char* lds) {
   const int lane = threadIdx.x & 63;
   const int i = lane & 15, g = lane >> 4;
   const int dh = p.dh, dm = p.dm;
   const int chunk = 2 * g + (i >> 3);
   const uint16_t* wx[1] = {W + static_cast<size_t>(j0 + (i & 7)) * dh + 8 * chunk};
   const uint16_t* wy[1] = {W + static_cast<size_t>(dm + j0 + (i & 7)) * dh + 8 * chunk};
-  TokenRows b[NT];
-  bool need_y[NT];
-  token_rows<NT>(static_cast<const uint16_t*>(p.hidden), p.sorted_token, row0, nrows, dh, b, need_y);
+  const TokenSource tok{static_cast<const uint16_t*>(p.hidden), p.sorted_token, row0, nrows, dh};
   f32x4 acc[1][NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[0][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tile<1, NT, U, false>(wx, wy, b, need_y, 0, 0, dh, start_rotation(dh), acc);
+  stream_tiles<1, NT, KC, false>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC), lds, acc);
 
   uint16_t* h = reinterpret_cast<uint16_t*>(p.h);
 #pragma unroll
@@ -242,6 +287,7 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W
 
 // grid (dm / 32, M + n_sh), 256 threads: 4 wavefronts x 8 intermediate indices
 __global__ __launch_bounds__(256) void ffn_gateup_mfma(FfnArgs p) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
   const int w = blockIdx.y;
   if (w >= *p.n_work) return;
   const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
@@ -249,11 +295,11 @@ __global__ __launch_bounds__(256) void ffn_gateup_mfma(FfnArgs p) {
       expert_base<SERE_BF16>(p.w_gate_up, p.shared_gate_up, e, p.M, static_cast<size_t>(2) * p.dm * p.dh));
   const int j0 = (blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kGateUpJ;
   if (cnt <= kTile) {
-    gateup_group<1, 4>(p, W, j0, off, cnt);
+    gateup_group<1, 256>(p, W, j0, off, cnt, lds);
   } else if (cnt <= 2 * kTile) {
-    gateup_group<2, 2>(p, W, j0, off, cnt);
+    gateup_group<2, 256>(p, W, j0, off, cnt, lds);
   } else {
-    for (int q = 0; q < cnt; q += 4 * kTile) gateup_group<4, 2>(p, W, j0, off + q, min(4 * kTile, cnt - q));
+    for (int q = 0; q < cnt; q += 4 * kTile) gateup_group<4, 128>(p, W, j0, off + q, min(4 * kTile, cnt - q), lds);
   }
 }
 
@@ -263,24 +309,26 @@ __global__ __launch_bounds__(256) void ffn_gateup_mfma(FfnArgs p) {
 // operand is h_hi + h_lo (two MFMAs per weight fragment).  Partial results go
 // to y[slice][row][r] (fp32).
 // ---------------------------------------------------------------------------
-template <int NT, int U, bool LO>
+template <int NT, int KC, bool LO>
 __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, int r0, int kbeg, int kend,
-                                           int slice, int row0, int nrows) {
+                                           int slice, int row0, int nrows, unsigned char* lds) {
   const int lane = threadIdx.x & 63;
   const int i = lane & 15, g = lane >> 4;
   const int dh = p.dh, dm = p.dm;
   const int chunk = 2 * g + (i >> 3);
-  const uint16_t* base = W + static_cast<size_t>(r0 + (i & 7)) * dm + 8 * chunk;
+  // a workgroup whose last wavefronts fall beyond d_h (d_h is a multiple of 64, not of 128)
+  // still takes part in the staging; those wavefronts stream row block 0 again and store nothing
+  const bool live = r0 < dh;
+  const uint16_t* base = W + static_cast<size_t>((live ? r0 : 0) + (i & 7)) * dm + 8 * chunk;
   const uint16_t* wx[2] = {base, base + static_cast<size_t>(16) * dm};
   const uint16_t* wy[2] = {base + static_cast<size_t>(8) * dm, base + static_cast<size_t>(24) * dm};
-  TokenRows b[NT];
-  bool need_y[NT];
-  token_rows<NT>(reinterpret_cast<const uint16_t*>(p.h), nullptr, row0, nrows, dm, b, need_y);
+  const TokenSource tok{reinterpret_cast<const uint16_t*>(p.h), nullptr, row0, nrows, dm};
   f32x4 acc[2][NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[0][t] = acc[1][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tile<2, NT, U, LO>(wx, wy, b, need_y, static_cast<size_t>(p.rows) * dm, kbeg, kend,
-                            start_rotation(kend - kbeg), acc);
+  stream_tiles<2, NT, KC, LO>(wx, wy, tok, static_cast<size_t>(p.rows) * dm, kbeg, kend,
+                              start_rotation(kend - kbeg, KC), lds, acc);
+  if (!live) return;
   float* y = p.y + static_cast<size_t>(slice) * p.rows * dh;
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
@@ -293,8 +341,9 @@ __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, 
   }
 }
 
-// grid ((dh / 128) * ksplit, M + n_sh), 256 threads: 4 wavefronts x 32 output rows
+// grid (ceil(dh / 128) * ksplit, M + n_sh), 256 threads: 4 wavefronts x 32 output rows
 __global__ __launch_bounds__(256) void ffn_down_mfma(FfnArgs p) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
   const int w = blockIdx.y;
   if (w >= *p.n_work) return;
   const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
@@ -302,24 +351,23 @@ __global__ __launch_bounds__(256) void ffn_down_mfma(FfnArgs p) {
       expert_base<SERE_BF16>(p.w_down, p.shared_down, e, p.M, static_cast<size_t>(p.dh) * p.dm));
   const int slab = blockIdx.x / p.ksplit, slice = blockIdx.x % p.ksplit;
   const int r0 = (slab * kWavesPerBlock + (threadIdx.x >> 6)) * kDownRows;
-  if (r0 >= p.dh) return;  // d_h is a multiple of 64, not necessarily of 128
   // this slice of d_m, in 64-wide blocks
   const int blocks = p.dm >> 6, per = (blocks + p.ksplit - 1) / p.ksplit;
   const int kbeg = min(slice * per, blocks) << 6, kend = min((slice + 1) * per, blocks) << 6;
   if (p.split_h) {
     if (cnt <= kTile) {
-      down_group<1, 4, true>(p, W, r0, kbeg, kend, slice, off, cnt);
+      down_group<1, 128, true>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
     } else {
       for (int q = 0; q < cnt; q += 2 * kTile)
-        down_group<2, 2, true>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q));
+        down_group<2, 64, true>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
     }
   } else if (cnt <= kTile) {
-    down_group<1, 4, false>(p, W, r0, kbeg, kend, slice, off, cnt);
+    down_group<1, 128, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
   } else if (cnt <= 2 * kTile) {
-    down_group<2, 2, false>(p, W, r0, kbeg, kend, slice, off, cnt);
+    down_group<2, 128, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
   } else {
     for (int q = 0; q < cnt; q += 4 * kTile)
-      down_group<4, 2, false>(p, W, r0, kbeg, kend, slice, off + q, min(4 * kTile, cnt - q));
+      down_group<4, 64, false>(p, W, r0, kbeg, kend, slice, off + q, min(4 * kTile, cnt - q), lds);
   }
 }
 
