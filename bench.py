@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-sere", action="store_true",
                     help="time only the headline SERE step (for per-kernel profiles)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="with --only-sere: also run a plain 256 MiB device copy 4 times, so that a "
+                         "counter run holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -196,6 +199,12 @@ def main():
 
     sere = measure("sere", args.S, args.rho, args.steps, args.warmup)
     if args.only_sere:
+        if args.copy_calibration:
+            src = torch.ones(128 << 20, dtype=torch.bfloat16, device="cuda")   # 256 MiB
+            dst = torch.empty_like(src)
+            for _ in range(4):
+                dst.copy_(src)
+            torch.cuda.synchronize()
         print(json.dumps({"sere": sere}))
         return
     base = measure("baseline", spec.top_k, 0.0, args.steps, args.warmup)
