@@ -58,6 +58,37 @@ __device__ __forceinline__ void load8<SERE_BF16>(const void* base, size_t idx, f
   v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
 }
 
+// The same eight elements kept as loaded (bf16: one 128-bit register group),
+// to be widened later: lets many loads be in flight in few registers.
+template <int DT>
+struct Raw8;
+template <>
+struct Raw8<SERE_F32> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const void* base, size_t idx) {
+    const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(base) + idx);
+    a = p[0];
+    b = p[1];
+  }
+  __device__ __forceinline__ void widen(float (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+template <>
+struct Raw8<SERE_BF16> {
+  uint4 q;
+  __device__ __forceinline__ void load(const void* base, size_t idx) {
+    q = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + idx);
+  }
+  __device__ __forceinline__ void widen(float (&v)[8]) const {
+    v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+    v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+    v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+    v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+  }
+};
+
 template <int DT>
 __device__ __forceinline__ void store1(void* base, size_t idx, float v);
 template <>

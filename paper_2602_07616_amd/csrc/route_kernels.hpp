@@ -79,56 +79,103 @@ __device__ __forceinline__ double key_to_double(uint64_t k) {
   return __longlong_as_double(static_cast<long long>(b));
 }
 
+// value of the lane D places further round in the 16-lane row (DPP row rotate)
+template <int D>
+__device__ __forceinline__ uint32_t row_rot(uint32_t v) {
+  return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x120 + D, 0xF, 0xF, true));
+}
+template <int D>
+__device__ __forceinline__ void rank_step(uint64_t key, uint32_t id, uint32_t& rank) {
+  const uint64_t okey = (static_cast<uint64_t>(row_rot<D>(static_cast<uint32_t>(key >> 32))) << 32) |
+                        row_rot<D>(static_cast<uint32_t>(key));
+  const uint32_t oid = row_rot<D>(id);
+  rank += (okey > key || (okey == key && oid < id)) ? 1u : 0u;
+  if constexpr (D < 15) rank_step<D + 1>(key, id, rank);
+}
+
 // ---------------------------------------------------------------------------
-// Router logits in fp64.  grid (ceil(M/16), T), 256 threads; wave w of block
-// (bx, t) computes experts bx*16 + 4w .. +3 for token t, the four dot products
-// interleaved.  Every logit is reduced in the same lane pattern, so
-// bit-identical router rows give bit-identical logits (ties then resolve by
-// index, as in exact arithmetic).  Block (0,0) clears the int32 at clear_word.
+// Router logits in fp64, delivered as SORTED LISTS.  grid (ceil(M/16), T),
+// 256 threads; wave w of block (bx, t) computes experts bx*16 + 4w .. +3 for
+// token t, the four dot products interleaved.  Every logit is reduced in the
+// same lane pattern, so bit-identical router rows give bit-identical logits
+// (ties then resolve by index, as in exact arithmetic).  The block then ranks
+// its 16 logits (larger first, equal: lower expert first) and writes them as
+// order-preserving keys with their expert ids:
+//   list_key[(t*L + bx)*16 + rank], list_id[(t*L + bx)*16 + rank],  L = gridDim.x;
+// places of experts >= M hold key 0 (below every real key).
+// Block (0,0) clears the int32 at clear_word.
 // ---------------------------------------------------------------------------
 template <int DT>
 __global__ __launch_bounds__(256) void router_logits_kernel(
-    const void* __restrict__ hidden, const void* __restrict__ router_w, double* __restrict__ logits,
-    int T, int M, int dh, int32_t* clear_word) {
+    const void* __restrict__ hidden, const void* __restrict__ router_w, uint64_t* __restrict__ list_key,
+    uint8_t* __restrict__ list_id, int T, int M, int dh, int32_t* clear_word) {
+  __shared__ double s_logit[16];
   const int t = blockIdx.y;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   if (clear_word != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *clear_word = 0;
   const int e0 = blockIdx.x * 16 + wave * 4;
-  if (e0 >= M) return;
   double acc[4] = {0.0, 0.0, 0.0, 0.0};
-  for (int i = lane * 8; i < dh; i += 512) {
-    float xv[8];
-    load8<DT>(hidden, static_cast<size_t>(t) * dh + i, xv);
-    double xd[8];
+  // four 512-wide chunks per pass, all loads of a pass issued before any arithmetic
+  // (the router weights come cold from HBM on every step; one round trip instead of four)
+  for (int i0 = lane * 8; i0 < dh; i0 += 2048) {
+    Raw8<DT> xr[4], wr[4][4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) xd[j] = static_cast<double>(xv[j]);
+    for (int c = 0; c < 4; ++c) {
+      const int i = i0 + 512 * c;
+      if (i < dh) {
+        xr[c].load(hidden, static_cast<size_t>(t) * dh + i);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (e0 + q < M) {  // wave-uniform
-        float wv[8];
-        load8<DT>(router_w, static_cast<size_t>(e0 + q) * dh + i, wv);
+        for (int q = 0; q < 4; ++q)
+          if (e0 + q < M) wr[c][q].load(router_w, static_cast<size_t>(e0 + q) * dh + i);  // wave-uniform
+      }
+    }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[q] = fma(xd[j], static_cast<double>(wv[j]), acc[q]);
+    for (int c = 0; c < 4; ++c) {
+      if (i0 + 512 * c < dh) {
+        float xv[8];
+        xr[c].widen(xv);
+        double xd[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) xd[j] = static_cast<double>(xv[j]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (e0 + q < M) {
+            float wv[8];
+            wr[c][q].widen(wv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[q] = fma(xd[j], static_cast<double>(wv[j]), acc[q]);
+          }
+        }
       }
     }
   }
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    if (e0 + q < M) {
-      const double s = wave_sum_dpp(acc[q]);
-      if (lane == 0) logits[static_cast<size_t>(t) * M + e0 + q] = s;
-    }
+    const double sum = wave_sum_dpp(acc[q]);
+    if (lane == 0) s_logit[wave * 4 + q] = sum;
+  }
+  __syncthreads();
+  if (threadIdx.x < 16) {  // one 16-lane row; the other rows of the wavefront idle
+    const int e = blockIdx.x * 16 + threadIdx.x;
+    const uint64_t key = e < M ? sortable_key(s_logit[threadIdx.x]) : 0ull;
+    uint32_t rank = 0;
+    rank_step<1>(key, static_cast<uint32_t>(e), rank);
+    const size_t at = (static_cast<size_t>(t) * gridDim.x + blockIdx.x) * 16 + rank;
+    list_key[at] = key;
+    list_id[at] = static_cast<uint8_t>(e);
   }
 }
 
 // ---------------------------------------------------------------------------
-// Ordered top-K and gate.  A 16-lane row of a wavefront owns one token (four
-// tokens per wavefront); lane i of the row holds experts i, i+16, ... (NC per
-// lane, M <= 16*NC).  K rounds of arg-max over the not-yet-taken logits: the
-// larger logit wins, equal logits go to the lower expert index; the row-wide
-// arg-max is four DPP exchanges.  Gate = softmax over the K selected logits
-// (fp64 internally, stored fp32).  `row` is NULL for a row without a token.
-// ids8 (may be NULL) receives the ids as bytes for the workgroup's own use.
+// Ordered top-K and gate by merging the sorted lists.  LP (4, 8 or 16) adjacent
+// lanes own one token, lane l of the group holds list l (all 16 entries, in
+// registers).  K rounds: the group's arg-max over the list heads (log2 LP DPP
+// exchanges; larger key wins, equal keys go to the lower expert id), the
+// winning lane pops its head.  Gate = softmax over the K selected logits (fp64
+// internally, stored fp32); lane l keeps the selected logits of ranks
+// l, l + LP, ... (KS of them, K <= KS*LP).  `active` is false for a group
+// without a token.  ids8 (may be NULL) receives the ids as bytes for the
+// workgroup's own use.
 // ---------------------------------------------------------------------------
 template <int STEP>
 __device__ __forceinline__ void argmax_step(uint64_t& key, uint32_t& idx) {
@@ -142,67 +189,83 @@ __device__ __forceinline__ void argmax_step(uint64_t& key, uint32_t& idx) {
   }
 }
 
-template <int NC>
-__device__ __forceinline__ void topk_gate_row(const double* __restrict__ row, int32_t* __restrict__ ids,
-                                              float* __restrict__ w, uint8_t* ids8, int M, int K) {
-  const int i = threadIdx.x & 15;
-  uint64_t cand[NC];
-  uint32_t taken = 0;
+template <int LP>
+__device__ __forceinline__ double group_sum(double v) {
+  v += row_xchg<0>(v);
+  v += row_xchg<1>(v);
+  if constexpr (LP >= 8) v += row_xchg<2>(v);
+  if constexpr (LP >= 16) v += row_xchg<3>(v);
+  return v;
+}
+
+template <int LP, int KS>
+__device__ __forceinline__ void topk_merge(const uint64_t* __restrict__ list_key,
+                                           const uint8_t* __restrict__ list_id, bool active, int nlists,
+                                           int32_t* __restrict__ ids, float* __restrict__ w, uint8_t* ids8, int K) {
+  const int l = threadIdx.x & (LP - 1);
+  const bool has_list = active && l < nlists;
+  uint64_t key[16];
+  uint32_t idw[4];  // 16 expert ids, one byte each
+  if (has_list) {
+    const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(list_key + static_cast<size_t>(l) * 16);
 #pragma unroll
-  for (int c = 0; c < NC; ++c) {
-    const int e = i + 16 * c;
-    if (row != nullptr && e < M) {
-      cand[c] = sortable_key(row[e]);
-    } else {
-      cand[c] = 0;  // below every real key (0 would be the pattern of a NaN)
-      taken |= 1u << c;
+    for (int j = 0; j < 8; ++j) {
+      const ulonglong2 v = kp[j];
+      key[2 * j] = v.x;
+      key[2 * j + 1] = v.y;
     }
-  }
-  double mysel[NC];  // selected logit of rank k = i + 16*c
+    const uint4 iv = *reinterpret_cast<const uint4*>(list_id + static_cast<size_t>(l) * 16);
+    idw[0] = iv.x; idw[1] = iv.y; idw[2] = iv.z; idw[3] = iv.w;
+  } else {
 #pragma unroll
-  for (int c = 0; c < NC; ++c) mysel[c] = 0.0;
+    for (int j = 0; j < 16; ++j) key[j] = 0;
+    idw[0] = idw[1] = idw[2] = idw[3] = 0;
+  }
+  double mysel[KS];
+#pragma unroll
+  for (int c = 0; c < KS; ++c) mysel[c] = 0.0;
   double top = 0.0;
   for (int k = 0; k < K; ++k) {
-    uint64_t key = 0;
-    uint32_t idx = 0x7fffffffu;
+    uint64_t wkey = key[0];
+    uint32_t wid = key[0] != 0 ? (idw[0] & 0xffu) : 0x7fffffffu;
+    argmax_step<0>(wkey, wid);
+    argmax_step<1>(wkey, wid);
+    if constexpr (LP >= 8) argmax_step<2>(wkey, wid);
+    if constexpr (LP >= 16) argmax_step<3>(wkey, wid);
+    // every lane of the group now holds the winner; its owner pops
+    if (key[0] != 0 && (idw[0] & 0xffu) == wid) {
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const bool ok = !((taken >> c) & 1u);
-      if (ok && (idx == 0x7fffffffu || cand[c] > key)) {  // strict '>' keeps the lower index
-        key = cand[c];
-        idx = i + 16 * c;
-      }
+      for (int j = 0; j < 15; ++j) key[j] = key[j + 1];
+      key[15] = 0;
+      idw[0] = (idw[0] >> 8) | (idw[1] << 24);
+      idw[1] = (idw[1] >> 8) | (idw[2] << 24);
+      idw[2] = (idw[2] >> 8) | (idw[3] << 24);
+      idw[3] >>= 8;
     }
-    argmax_step<0>(key, idx);
-    argmax_step<1>(key, idx);
-    argmax_step<2>(key, idx);
-    argmax_step<3>(key, idx);
-    // every lane of the row now holds the winner
-    const double val = key_to_double(key);
-    if ((idx & 15u) == static_cast<uint32_t>(i)) taken |= 1u << (idx >> 4);
+    const double val = key_to_double(wkey);
     if (k == 0) top = val;
 #pragma unroll
-    for (int c = 0; c < NC; ++c)
-      if (k == i + 16 * c) mysel[c] = val;
-    if (i == 0 && row != nullptr) {
-      ids[k] = static_cast<int32_t>(idx);
-      if (ids8 != nullptr) ids8[k] = static_cast<uint8_t>(idx);
+    for (int c = 0; c < KS; ++c)
+      if (k == l + LP * c) mysel[c] = val;
+    if (l == 0 && active) {
+      ids[k] = static_cast<int32_t>(wid);
+      if (ids8 != nullptr) ids8[k] = static_cast<uint8_t>(wid);
     }
   }
-  double ex[NC];
+  double ex[KS];
   double part = 0.0;
 #pragma unroll
-  for (int c = 0; c < NC; ++c) {
+  for (int c = 0; c < KS; ++c) {
     ex[c] = 0.0;
-    if (16 * c < K) {  // uniform
-      ex[c] = (i + 16 * c < K) ? exp(mysel[c] - top) : 0.0;
+    if (LP * c < K) {  // uniform
+      ex[c] = (l + LP * c < K) ? exp(mysel[c] - top) : 0.0;
       part += ex[c];
     }
   }
-  const double denom = row_sum(part);
+  const double denom = group_sum<LP>(part);
 #pragma unroll
-  for (int c = 0; c < NC; ++c)
-    if (i + 16 * c < K && row != nullptr) w[i + 16 * c] = static_cast<float>(ex[c] / denom);
+  for (int c = 0; c < KS; ++c)
+    if (l + LP * c < K && active) w[l + LP * c] = static_cast<float>(ex[c] / denom);
 }
 
 // ---------------------------------------------------------------------------
@@ -231,7 +294,6 @@ struct RouteArgs {
 
 constexpr int kRouteThreads = 1024;
 constexpr int kRouteWaves = kRouteThreads / kWave;
-constexpr int kTokensPerBlock = 4 * kRouteWaves;  // one 16-lane row per token
 constexpr int kIdsInLds = 4096;                   // slots whose ids a lone workgroup keeps in LDS
 
 struct RouteShared {
@@ -478,27 +540,32 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs p) {
   route_phase<false>(p, s, pf);
 }
 
-// Top-K + gate (64 tokens per workgroup), then the batch-wide step by the
-// workgroup that takes the last ticket.  With a single workgroup (T <= 64)
-// there is no ticket and the ids go from the top-K to the batch-wide step
-// through LDS.  grid ceil(T/64), 1024 threads; *ticket must be 0 at launch.
-// NC = ceil(M / 16) rounded up to 4, 8 or 16.
-template <int NC>
-__global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const double* __restrict__ logits,
+// Top-K + gate (1024 / LP tokens per workgroup), then the batch-wide step by
+// the workgroup that takes the last ticket.  With a single workgroup there is
+// no ticket and the ids go from the top-K to the batch-wide step through LDS.
+// grid ceil(T*LP/1024), 1024 threads; *ticket must be 0 at launch.
+// LP = lanes per token >= number of lists (4, 8, 16); K <= KS*LP.
+template <int LP, int KS>
+__global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const uint64_t* __restrict__ list_key,
+                                                                   const uint8_t* __restrict__ list_id,
                                                                    int32_t* __restrict__ topk_ids,
                                                                    float* __restrict__ topk_w, int32_t* ticket,
                                                                    RouteArgs p) {
   __shared__ RouteShared s;
+  constexpr int NC = LP;  // the similarity scan uses the same bound M <= 16*LP
+  constexpr int kTokens = kRouteThreads / LP;
   SimPrefetch<NC> pf;
   prefetch_sim(p, pf);
-  const int t = blockIdx.x * kTokensPerBlock + (threadIdx.x >> 4);
+  const int nlists = (p.M + 15) >> 4;
+  const int t = blockIdx.x * kTokens + threadIdx.x / LP;
   const bool lone = gridDim.x == 1 && p.T * p.K <= kIdsInLds;
   const bool has = t < p.T;
-  if (blockIdx.x * kTokensPerBlock + 4 * (threadIdx.x >> 6) < p.T)  // wave-uniform: the wavefront has a token
-    topk_gate_row<NC>(has ? logits + static_cast<size_t>(t) * p.M : nullptr,
-                      topk_ids + static_cast<size_t>(has ? t : 0) * p.K,
-                      topk_w + static_cast<size_t>(has ? t : 0) * p.K,
-                      lone ? s.ids8 + static_cast<size_t>(has ? t : 0) * p.K : nullptr, p.M, p.K);
+  const int first_of_wave = blockIdx.x * kTokens + (threadIdx.x >> 6) * (kWave / LP);
+  if (first_of_wave < p.T) {  // wave-uniform: the wavefront has a token
+    const size_t tt = has ? t : 0;
+    topk_merge<LP, KS>(list_key + tt * nlists * 16, list_id + tt * nlists * 16, has, nlists, topk_ids + tt * p.K,
+                       topk_w + tt * p.K, lone ? s.ids8 + tt * p.K : nullptr, p.K);
+  }
   if (lone) {
     __syncthreads();
     route_phase<true>(p, s, pf);

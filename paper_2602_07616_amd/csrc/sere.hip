@@ -15,7 +15,7 @@ namespace sere {
 
 // ---------------------------------------------------------------- layout ---
 struct Layout {
-  size_t logits, topk_ids, topk_w, rerouted, cnt_before, cnt_after, primary, num_active, offsets,
+  size_t list_key, list_id, topk_ids, topk_w, rerouted, cnt_before, cnt_after, primary, num_active, offsets,
       sorted_token, sorted_slot, slot_pos, work_expert, work_off, work_cnt, n_work, ticket, h, y, total;
   int rows;    // A + n_sh*T rows of the sorted slot list
   int ksplit;  // slices of d_m in the down projection
@@ -42,7 +42,9 @@ static Layout make_layout(const sere_config& c) {
     o = align_up(o + bytes);
     return at;
   };
-  l.logits = take(T * M * sizeof(double));
+  const size_t lists = (M + 15) / 16;  // sorted 16-expert lists per token
+  l.list_key = take(T * lists * 16 * sizeof(uint64_t));
+  l.list_id = take(T * lists * 16);
   l.topk_ids = take(A * 4);
   l.topk_w = take(A * 4);
   l.rerouted = take(A * 4);
@@ -158,7 +160,8 @@ struct StageTimer {
 
 // --------------------------------------------------------------- launches ---
 struct Pointers {
-  double* logits;
+  uint64_t* list_key;
+  uint8_t* list_id;
   int32_t* ticket;
   int32_t* topk_ids;
   float* topk_w;
@@ -173,7 +176,8 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
   static const sere_route_out none{};
   if (o == nullptr) o = &none;
   Pointers p{};
-  p.logits = reinterpret_cast<double*>(ws + l.logits);
+  p.list_key = reinterpret_cast<uint64_t*>(ws + l.list_key);
+  p.list_id = reinterpret_cast<uint8_t*>(ws + l.list_id);
   p.ticket = reinterpret_cast<int32_t*>(ws + l.ticket);
   p.topk_ids = static_cast<int32_t*>(pick(o->topk_ids, l.topk_ids));
   p.topk_w = static_cast<float*>(pick(o->topk_weights, l.topk_w));
@@ -211,11 +215,11 @@ static int launch_router(const sere_config& c, const Pointers& p, const void* hi
     StageTimer tm(SERE_STAGE_ROUTER, s);
     dim3 grid((c.num_experts + 15) / 16, c.num_tokens);
     if (c.dtype == SERE_F32)
-      hipLaunchKernelGGL(router_logits_kernel<SERE_F32>, grid, dim3(256), 0, s, hidden, router_w, p.logits,
-                         c.num_tokens, c.num_experts, c.hidden, p.ticket);
+      hipLaunchKernelGGL(router_logits_kernel<SERE_F32>, grid, dim3(256), 0, s, hidden, router_w, p.list_key,
+                         p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
     else
-      hipLaunchKernelGGL(router_logits_kernel<SERE_BF16>, grid, dim3(256), 0, s, hidden, router_w, p.logits,
-                         c.num_tokens, c.num_experts, c.hidden, p.ticket);
+      hipLaunchKernelGGL(router_logits_kernel<SERE_BF16>, grid, dim3(256), 0, s, hidden, router_w, p.list_key,
+                         p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
   }
   return hip_status();
 }
@@ -225,16 +229,22 @@ static int launch_route(const sere_config& c, const Pointers& p, bool with_topk,
   {
     StageTimer tm(SERE_STAGE_ROUTE, s);
     if (with_topk) {
-      const dim3 grid((c.num_tokens + kTokensPerBlock - 1) / kTokensPerBlock);
-      if (c.num_experts <= 64)
-        hipLaunchKernelGGL(topk_route_kernel<4>, grid, dim3(kRouteThreads), 0, s, p.logits, p.topk_ids, p.topk_w,
-                           p.ticket, p.route);
-      else if (c.num_experts <= 128)
-        hipLaunchKernelGGL(topk_route_kernel<8>, grid, dim3(kRouteThreads), 0, s, p.logits, p.topk_ids, p.topk_w,
-                           p.ticket, p.route);
-      else
-        hipLaunchKernelGGL(topk_route_kernel<16>, grid, dim3(kRouteThreads), 0, s, p.logits, p.topk_ids, p.topk_w,
-                           p.ticket, p.route);
+      // lanes per token = lists per token rounded up to 4, 8 or 16; K <= KS * lanes
+      const int lists = (c.num_experts + 15) / 16;
+      const int lp = lists <= 4 ? 4 : (lists <= 8 ? 8 : 16);
+      const bool small_k = c.top_k <= 2 * lp;
+      const dim3 grid((c.num_tokens * lp + kRouteThreads - 1) / kRouteThreads);
+#define SERE_LAUNCH_TOPK(LP, KS)                                                                              \
+  hipLaunchKernelGGL((topk_route_kernel<LP, KS>), grid, dim3(kRouteThreads), 0, s, p.list_key, p.list_id, \
+                     p.topk_ids, p.topk_w, p.ticket, p.route)
+      if (lp == 4) {
+        if (small_k) SERE_LAUNCH_TOPK(4, 2); else SERE_LAUNCH_TOPK(4, 16);
+      } else if (lp == 8) {
+        if (small_k) SERE_LAUNCH_TOPK(8, 2); else SERE_LAUNCH_TOPK(8, 16);
+      } else {
+        if (small_k) SERE_LAUNCH_TOPK(16, 2); else SERE_LAUNCH_TOPK(16, 16);
+      }
+#undef SERE_LAUNCH_TOPK
     } else
       hipLaunchKernelGGL(route_kernel, dim3(1), dim3(kRouteThreads), 0, s, p.route);
     // the internal sorted_token list also carries the shared experts' rows; a
