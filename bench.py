@@ -52,12 +52,20 @@ class Runner:
     """One workload resident in HBM `copies` times; times steps of one entry point."""
 
     def __init__(self, wl, sim, copies, use_graph):
+        import numpy as np
         import torch
         from paper_2602_07616_amd import device
         self.torch = torch
         self.wl = wl
         self.use_graph = use_graph
-        first = device.DeviceLayer.from_workload(wl, sim, 1, 0.0)
+        weights = device.DeviceLayer.from_workload(wl, np.zeros((1, 1), np.float32), 1, 0.0).weights() \
+            if sim is None else None
+        if sim is None:
+            # the similarity matrix is part of the product path too: estimated on the GPU from the
+            # layer's own weights and seeded calibration tokens (untimed set-up, as in the paper)
+            sim = device.similarity_on_device(wl, weights)
+        first = device.DeviceLayer.from_workload(wl, sim, 1, 0.0, weights=weights)
+        self.sim = sim
         self.layers = [first]
         for _ in range(copies - 1):
             w = tuple(None if t is None else t.clone() for t in first.weights())
@@ -180,11 +188,11 @@ def main():
 
     spec = wk.SPECS[args.workload]
     wl = wk.make_workload(spec)
-    sim = similarity_for(wl)
     eb = spec.elem_bytes
     expert_bytes = spec.expert_bytes
     copies = args.copies or max(2, min(16, int(np.ceil(4.0e9 / (spec.experts * expert_bytes)))))
-    run = Runner(wl, sim, copies, not args.no_graph)
+    run = Runner(wl, None, copies, not args.no_graph)
+    sim_host = run.sim.cpu().numpy()
 
     def measure(mode, S, rho, steps, warmup):
         run.set_knobs(S, rho)
@@ -236,7 +244,7 @@ def main():
                    "experts": spec.experts, "top_k": spec.top_k, "inter": spec.inter,
                    "shared": spec.shared, "select_top_k": args.S, "threshold": args.rho,
                    "weight_copies": copies, "launch": "stream" if args.no_graph else "hip-graph",
-                   "similarity": SIM_KIND},
+                   "similarity": "Frobenius estimate on the GPU (sere_similarity) from seeded calibration tokens"},
         "sere": sere, "no_reroute": base,
         "speedup_vs_no_reroute": round(base["us_per_step"] / sere["us_per_step"], 3),
         "route_only_us": round(route_us, 2),
@@ -249,28 +257,21 @@ def main():
         result["grid"] = {f"S={S},rho={rho}": measure("sere", S, rho, args.steps, args.warmup)
                           for S, rho in spec.grid}
     if args.sweep:
-        result["sweep"] = sweep(args, sim)
+        result["sweep"] = sweep(args)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, sim, args.S, args.rho, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(wl, sim_host, args.S, args.rho, args.cpu_seconds)
     print(json.dumps(result))
 
 
-SIM_KIND = "planted (twin pairs 0.9, others < 0.4)"
-
-
-def similarity_for(wl):
-    """Similarity matrix fed to the timed steps."""
-    from paper_2602_07616_amd import workloads as wk
-    return wk.planted_similarity(wl.spec, wl.spec.weight_seed)
-
-
-def sweep(args, sim):
+def sweep(args):
     """Batch-size sweep on the Qwen3-shaped layer: active experts and latency."""
     from paper_2602_07616_amd import workloads as wk
     out = {}
+    sim = None
     for T in wk.BATCH_SWEEP:
         wl = wk.make_workload("qwen3_b128", tokens=T)
         run = Runner(wl, sim, 4, not args.no_graph)
+        sim = run.sim
         row = {}
         for label, mode, S in (("no_reroute", "baseline", 8), ("S=2", "sere", 2), ("S=1", "sere", 1)):
             run.set_knobs(S, 0.0)

@@ -177,6 +177,27 @@ int sere_moe_decode_baseline(const sere_config *cfg, const void *hidden, const v
                              size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Expert-similarity matrix of one layer from calibration tokens, with the
+ * Frobenius metric (Sec. 3.1.1 accumulation equation; appendix "Frobenius
+ * Similarity"; appendix algorithm "Expert Similarity Estimation"): for each of
+ * `num_batches` batches of `batch_tokens` tokens every routed expert is run on
+ * every token, x_pq = ||A_p - A_q||_F, Sim(p,q) = 1 - x_pq / max over all pairs
+ * of that batch, and sim = the mean of Sim over the batches (diagonal 1).
+ *   calib [num_batches, batch_tokens, d_h]  dtype, device
+ *   sim   [M, M] fp32, device, written
+ * Uses cfg->hidden, num_experts, inter, dtype (the other fields must be valid
+ * but are not used).  The experts run through the decode path's own FFN
+ * kernels, so for SERE_BF16 the activations carry bf16-level rounding (as a
+ * bf16 model forward does); similarities agree with an fp64 evaluation to a
+ * few 1e-3.  batch_tokens: 1 .. 4096, num_batches: 1 .. 4096.
+ * Workspace: sere_similarity_workspace_bytes(cfg, batch_tokens).
+ */
+size_t sere_similarity_workspace_bytes(const sere_config *cfg, int32_t batch_tokens);
+int sere_similarity(const sere_config *cfg, const void *calib, int32_t num_batches,
+                    int32_t batch_tokens, const void *w_gate_up, const void *w_down, float *sim,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every kernel the calls
  * above enqueue is bracketed by HIP events on the caller's stream (at most
  * SERE_TIMING_MAX_RECORDS launches are kept, later ones are not recorded).

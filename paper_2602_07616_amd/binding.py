@@ -74,6 +74,10 @@ def load() -> ctypes.CDLL:
     lib.sere_moe_decode.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, outp, vp, sz, vp]
     lib.sere_moe_decode_baseline.restype = ci
     lib.sere_moe_decode_baseline.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, outp, vp, sz, vp]
+    lib.sere_similarity_workspace_bytes.restype = sz
+    lib.sere_similarity_workspace_bytes.argtypes = [cfgp, ctypes.c_int32]
+    lib.sere_similarity.restype = ci
+    lib.sere_similarity.argtypes = [cfgp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, sz, vp]
     lib.sere_stage_timing.restype = ci
     lib.sere_stage_timing.argtypes = [ci]
     lib.sere_stage_timing_read.restype = ci
@@ -192,6 +196,17 @@ def sere_moe_decode_baseline(cfg, hidden, router_w, w_gate_up, w_down, shared_ga
         ctypes.byref(cfg), _ptr(hidden), _ptr(router_w), _ptr(w_gate_up), _ptr(w_down),
         _ptr(shared_gate_up), _ptr(shared_down), _ptr(out), _byref_or_null(o), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def sere_similarity_workspace_bytes(cfg: sere_config, batch_tokens: int) -> int:
+    return int(load().sere_similarity_workspace_bytes(ctypes.byref(cfg), batch_tokens))
+
+
+def sere_similarity(cfg, calib, num_batches, batch_tokens, w_gate_up, w_down, sim, workspace,
+                    stream=None) -> None:
+    _check(load().sere_similarity(ctypes.byref(cfg), _ptr(calib), num_batches, batch_tokens,
+                                  _ptr(w_gate_up), _ptr(w_down), _ptr(sim), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def sere_stage_timing(enable: bool) -> None:

@@ -91,7 +91,7 @@ struct Stage {
   static constexpr int kPerThread = kRows * kPiecesPerRow / 256;
   static_assert(kPerThread >= 1 && kRows * kPiecesPerRow % 256 == 0, "chunk must split over 256 threads");
 };
-constexpr int kStageLdsBytes = 2 * Stage<4, 128>::kBufBytes;  // the largest configuration, two buffers
+constexpr int kStageLdsBytes = 2 * Stage<2, 256>::kBufBytes;  // the largest configuration, two buffers
 
 // Token rows of a group: row r (< nrows) of the group is row index[first + r]
 // (or first + r if index is NULL) of a matrix with leading dimension ld.
@@ -120,13 +120,16 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
   constexpr int H0 = (KB + 1) / 2;     // k blocks in the first half of a chunk
   constexpr int NP = LO ? 2 : 1;
   static_assert(NP * 2 * St::kBufBytes <= kStageLdsBytes, "LDS budget");
-  const u32x4 zero = {0u, 0u, 0u, 0u};
   const int tid = threadIdx.x, lane = tid & 63;
   const int i = lane & 15, g = lane >> 4;
   const int len = kend - kbeg;
   const int nch = (len + KC - 1) / KC;
 
-  // this thread's pieces of a chunk: (row, 16-byte column) pairs, the same for every chunk
+  // This thread's pieces of a chunk: (row, 16-byte column) pairs, the same for every chunk.
+  // Every load below is unconditional (rows beyond nrows re-read row 0, columns beyond kend
+  // re-read the last valid ones; what they deliver is finite and never used): with loads
+  // under branches the compiler can no longer count outstanding loads and waits for ALL of
+  // them before every use, which would serialise the prefetch.
   const uint16_t* src[St::kPerThread];
   int dst[St::kPerThread], col[St::kPerThread];
 #pragma unroll
@@ -135,9 +138,8 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
     const int row = pc / St::kPiecesPerRow;
     col[j] = (pc % St::kPiecesPerRow) * 8;
     dst[j] = row * St::kRowBytes + col[j] * 2;
-    src[j] = row < tok.nrows
-                 ? tok.base + static_cast<size_t>(tok.index != nullptr ? tok.index[tok.first + row] : tok.first + row) * tok.ld
-                 : nullptr;
+    const int r = row < tok.nrows ? row : 0;
+    src[j] = tok.base + static_cast<size_t>(tok.index != nullptr ? tok.index[tok.first + r] : tok.first + r) * tok.ld;
   }
   auto chunk_start = [&](int c) {
     int cc = c + rot;
@@ -150,7 +152,7 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
     for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
       for (int j = 0; j < St::kPerThread; ++j)
-        stage[pl][j] = (src[j] != nullptr && k0 + col[j] < kend) ? load_reused(src[j] + pl * lo_plane + k0 + col[j]) : zero;
+        stage[pl][j] = load_reused(src[j] + pl * lo_plane + min(k0 + col[j], kend - 8));
   };
   auto store_tokens = [&](int buf) {
 #pragma unroll
@@ -164,18 +166,18 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
   auto fetch_weights = [&](u32x4 (&x)[NA][H0], u32x4 (&y)[NA][H0], int k0, int b0, int b1) {
 #pragma unroll
     for (int b = b0; b < b1; ++b) {
-      const int kk = k0 + 64 * b;
+      const int kk = min(k0 + 64 * b, kend - 64);
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
-        x[a][b - b0] = kk < kend ? load_weight(wx[a] + kk) : zero;  // wave-uniform condition
-        y[a][b - b0] = kk < kend ? load_weight(wy[a] + kk) : zero;
+        x[a][b - b0] = load_weight(wx[a] + kk);
+        y[a][b - b0] = load_weight(wy[a] + kk);
       }
     }
   };
   auto multiply = [&](const u32x4 (&x)[NA][H0], const u32x4 (&y)[NA][H0], int k0, int b0, int b1, int buf) {
 #pragma unroll
     for (int b = b0; b < b1; ++b) {
-      if (k0 + 64 * b < kend) {  // wave-uniform; skipped blocks hold no valid token data either
+      if (k0 + 64 * b < kend) {  // wave-uniform; a block beyond kend holds a duplicate of the last one
         u32x4 b_even[NP][NT], b_odd[NP][NT];
 #pragma unroll
         for (int pl = 0; pl < NP; ++pl)
@@ -208,19 +210,22 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
     fetch_weights(xa, ya, k0, 0, H0);
     if (KB > H0) fetch_weights(xb, yb, k0, H0, KB);
     store_tokens(0);
-    for (int c = 0; c < nch; ++c) {
+    for (int c = 0; c + 1 < nch; ++c) {  // every pass of this loop has a next chunk to fetch
       __syncthreads();  // chunk c is in LDS; nobody still reads the other buffer
-      const int k1 = c + 1 < nch ? chunk_start(c + 1) : kend;  // kend: nothing left to fetch
-      if (c + 1 < nch) fetch_tokens(k1);
+      const int k1 = chunk_start(c + 1);
+      fetch_tokens(k1);
       multiply(xa, ya, k0, 0, H0, c & 1);
-      if (c + 1 < nch) fetch_weights(xa, ya, k1, 0, H0);
+      fetch_weights(xa, ya, k1, 0, H0);
       if (KB > H0) {
         multiply(xb, yb, k0, H0, KB, c & 1);
-        if (c + 1 < nch) fetch_weights(xb, yb, k1, H0, KB);
+        fetch_weights(xb, yb, k1, H0, KB);
       }
-      if (c + 1 < nch) store_tokens((c + 1) & 1);
+      store_tokens((c + 1) & 1);
       k0 = k1;
     }
+    __syncthreads();
+    multiply(xa, ya, k0, 0, H0, (nch - 1) & 1);
+    if (KB > H0) multiply(xb, yb, k0, H0, KB, (nch - 1) & 1);
   }
   __syncthreads();  // the LDS buffers may be refilled by the caller's next group
 }
@@ -294,12 +299,12 @@ __global__ __launch_bounds__(256) void ffn_gateup_mfma(FfnArgs p) {
   const uint16_t* W = static_cast<const uint16_t*>(
       expert_base<SERE_BF16>(p.w_gate_up, p.shared_gate_up, e, p.M, static_cast<size_t>(2) * p.dm * p.dh));
   const int j0 = (blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kGateUpJ;
+  // the routing step cuts experts into items of at most 32 rows; longer items (the
+  // similarity estimation's) are served 32 rows at a time, streaming the weights again
   if (cnt <= kTile) {
     gateup_group<1, 256>(p, W, j0, off, cnt, lds);
-  } else if (cnt <= 2 * kTile) {
-    gateup_group<2, 256>(p, W, j0, off, cnt, lds);
   } else {
-    for (int q = 0; q < cnt; q += 4 * kTile) gateup_group<4, 128>(p, W, j0, off + q, min(4 * kTile, cnt - q), lds);
+    for (int q = 0; q < cnt; q += 2 * kTile) gateup_group<2, 256>(p, W, j0, off + q, min(2 * kTile, cnt - q), lds);
   }
 }
 
@@ -363,11 +368,9 @@ __global__ __launch_bounds__(256) void ffn_down_mfma(FfnArgs p) {
     }
   } else if (cnt <= kTile) {
     down_group<1, 128, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
-  } else if (cnt <= 2 * kTile) {
-    down_group<2, 128, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
   } else {
-    for (int q = 0; q < cnt; q += 4 * kTile)
-      down_group<4, 64, false>(p, W, r0, kbeg, kend, slice, off + q, min(4 * kTile, cnt - q), lds);
+    for (int q = 0; q < cnt; q += 2 * kTile)
+      down_group<2, 128, false>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
   }
 }
 

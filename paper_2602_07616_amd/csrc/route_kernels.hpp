@@ -286,14 +286,16 @@ struct RouteArgs {
   int32_t* sorted_token;    // [A + n_sh*T]
   int32_t* sorted_slot;     // [A]
   int32_t* slot_pos;        // [A]  position of slot a = t*K+k in the sorted list
-  int32_t* work_expert;     // [M + n_sh] surviving experts ascending, then M+s per shared
-  int32_t* work_off;        // [M + n_sh] first row of the item in the sorted list
-  int32_t* work_cnt;        // [M + n_sh] rows of the item
+  int32_t* work_expert;     // [max items] expert of each work item (M+s for shared expert s); experts
+                            //             ascending, an expert's rows cut into items of <= kItemRows
+  int32_t* work_off;        // [max items] first row of the item in the sorted list
+  int32_t* work_cnt;        // [max items] rows of the item (1 .. kItemRows)
   int32_t* n_work;          // [1]
 };
 
 constexpr int kRouteThreads = 1024;
 constexpr int kRouteWaves = kRouteThreads / kWave;
+constexpr int kItemRows = 32;                     // rows of the sorted slot list per FFN work item
 constexpr int kIdsInLds = 4096;                   // slots whose ids a lone workgroup keeps in LDS
 
 struct RouteShared {
@@ -304,6 +306,7 @@ struct RouteShared {
   int scan_cnt[SERE_MAX_EXPERTS / kWave];
   int scan_act[SERE_MAX_EXPERTS / kWave];
   int scan_before[SERE_MAX_EXPERTS / kWave];
+  int scan_items[SERE_MAX_EXPERTS / kWave];
   int cursor[SERE_MAX_EXPERTS];
   int round_cnt[kRouteWaves][SERE_MAX_EXPERTS];
   uint8_t ids8[kIdsInLds];
@@ -420,39 +423,46 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
   }
   lds_barrier();
 
-  // inclusive scans over experts: slots (-> offsets) and activity (-> work list
-  // rank); inside each of the first four wavefronts by shuffles, across them
-  // through four totals in LDS
+  // inclusive scans over experts: slots (-> offsets), activity (-> active
+  // count) and work items (an expert's rows are cut into items of at most
+  // kItemRows rows, so that one long expert cannot hold up the FFN kernels);
+  // inside each of the first four wavefronts by shuffles, across them through
+  // four totals in LDS
   const bool is_e = tid < SERE_MAX_EXPERTS;
   const int my_cnt = (is_e && tid < M) ? s.cnt_a[tid] : 0;
   const int my_act = my_cnt > 0 ? 1 : 0;
-  int inc_cnt = my_cnt, inc_act = my_act;
+  const int my_items = (my_cnt + kItemRows - 1) / kItemRows;
+  int inc_cnt = my_cnt, inc_act = my_act, inc_items = my_items;
   if (is_e) {  // wave-uniform (waves 0-3)
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
       const int uc = __shfl_up(inc_cnt, d, kWave), ua = __shfl_up(inc_act, d, kWave);
+      const int ui = __shfl_up(inc_items, d, kWave);
       if (lane >= d) {
         inc_cnt += uc;
         inc_act += ua;
+        inc_items += ui;
       }
     }
     if (lane == kWave - 1) {
       s.scan_cnt[wave] = inc_cnt;
       s.scan_act[wave] = inc_act;
+      s.scan_items[wave] = inc_items;
     }
     const int nb = __popcll(__ballot(tid < M && s.cnt_b[tid] > 0));
     if (lane == 0) s.scan_before[wave] = nb;
   }
   lds_barrier();
-  int n_after = 0, n_before = 0;
+  int n_after = 0, n_before = 0, n_items = 0;
 #pragma unroll
   for (int w = 0; w < SERE_MAX_EXPERTS / kWave; ++w) {
     if (is_e && w < wave) {
       inc_cnt += s.scan_cnt[w];
-      inc_act += s.scan_act[w];
+      inc_items += s.scan_items[w];
     }
     n_after += s.scan_act[w];
     n_before += s.scan_before[w];
+    n_items += s.scan_items[w];
   }
   if (is_e && tid < M) {
     const int off = inc_cnt - my_cnt;
@@ -461,23 +471,25 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
     p.count_before[tid] = s.cnt_b[tid];
     p.count_after[tid] = my_cnt;
     p.primary_mask[tid] = s.prim[tid];
-    if (my_act) {
-      const int i = inc_act - 1;
-      p.work_expert[i] = tid;
-      p.work_off[i] = off;
-      p.work_cnt[i] = my_cnt;
+    const int first = inc_items - my_items;
+    for (int j = 0; j < my_items; ++j) {
+      p.work_expert[first + j] = tid;
+      p.work_off[first + j] = off + j * kItemRows;
+      p.work_cnt[first + j] = min(kItemRows, my_cnt - j * kItemRows);
     }
   }
+  const int sh_items = (p.T + kItemRows - 1) / kItemRows;  // per shared expert
   if (tid == 0) {
     p.expert_offsets[M] = A;
     p.num_active[0] = n_before;
     p.num_active[1] = n_after;
-    p.n_work[0] = n_after + p.n_sh;
+    p.n_work[0] = n_items + p.n_sh * sh_items;
   }
-  if (tid < p.n_sh) {
-    p.work_expert[n_after + tid] = M + tid;
-    p.work_off[n_after + tid] = A + tid * p.T;
-    p.work_cnt[n_after + tid] = p.T;
+  for (int i = tid; i < p.n_sh * sh_items; i += kRouteThreads) {
+    const int sh = i / sh_items, j = i % sh_items;
+    p.work_expert[n_items + i] = M + sh;
+    p.work_off[n_items + i] = A + sh * p.T + j * kItemRows;
+    p.work_cnt[n_items + i] = min(kItemRows, p.T - j * kItemRows);
   }
   for (int i = tid; i < p.n_sh * p.T; i += kRouteThreads) p.sorted_token[A + i] = i % p.T;
   lds_barrier();

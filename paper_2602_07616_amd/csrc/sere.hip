@@ -10,6 +10,7 @@
 #include "ffn_generic.hpp"
 #include "ffn_mfma.hpp"
 #include "route_kernels.hpp"
+#include "similarity_kernels.hpp"
 
 namespace sere {
 
@@ -17,8 +18,9 @@ namespace sere {
 struct Layout {
   size_t list_key, list_id, topk_ids, topk_w, rerouted, cnt_before, cnt_after, primary, num_active, offsets,
       sorted_token, sorted_slot, slot_pos, work_expert, work_off, work_cnt, n_work, ticket, h, y, total;
-  int rows;    // A + n_sh*T rows of the sorted slot list
-  int ksplit;  // slices of d_m in the down projection
+  int rows;      // A + n_sh*T rows of the sorted slot list
+  int ksplit;    // slices of d_m in the down projection
+  int max_work;  // upper bound on FFN work items (the FFN grids are sized for it)
 };
 
 static size_t align_up(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
@@ -33,9 +35,11 @@ static Layout make_layout(const sere_config& c) {
   Layout l{};
   const size_t T = c.num_tokens, M = c.num_experts, K = c.top_k, A = T * K;
   const size_t R = A + static_cast<size_t>(c.num_shared) * T;
-  const size_t W = M + c.num_shared;
+  // an expert's rows are cut into items of <= kItemRows: at most one partial item per expert
+  const size_t W = M + c.num_shared + R / kItemRows;
   l.rows = static_cast<int>(R);
   l.ksplit = down_ksplit(c);
+  l.max_work = static_cast<int>(W);
   size_t o = 0;
   auto take = [&](size_t bytes) {
     size_t at = o;
@@ -266,32 +270,42 @@ static void launch_combine(const sere_config& c, const Layout& l, const Pointers
 }
 
 // fp32 layers: vector-ALU kernels.  bf16 layers: matrix-core kernels.
-static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
-                       hipStream_t s) {
-  const int max_work = c.num_experts + c.num_shared;
-  if (c.dtype == SERE_F32) {
+static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, int ksplit, const FfnArgs& f,
+                               hipStream_t s) {
+  if (dtype == SERE_F32) {
     {
       StageTimer tm(SERE_STAGE_GATE_UP, s);
-      hipLaunchKernelGGL(ffn_gateup_generic<SERE_F32>, dim3((c.inter + kGenJB - 1) / kGenJB, max_work), dim3(256),
-                         0, s, f);
+      hipLaunchKernelGGL(ffn_gateup_generic<SERE_F32>, dim3((inter + kGenJB - 1) / kGenJB, max_work), dim3(256), 0, s,
+                         f);
     }
     {
       StageTimer tm(SERE_STAGE_DOWN, s);
-      hipLaunchKernelGGL(ffn_down_generic<SERE_F32>, dim3((c.hidden + kGenRB - 1) / kGenRB, max_work), dim3(256),
-                         0, s, f);
+      hipLaunchKernelGGL(ffn_down_generic<SERE_F32>, dim3((hidden + kGenRB - 1) / kGenRB, max_work), dim3(256), 0, s,
+                         f);
     }
   } else {
     {
       StageTimer tm(SERE_STAGE_GATE_UP, s);
-      hipLaunchKernelGGL(ffn_gateup_mfma, dim3(c.inter / (kGateUpJ * kWavesPerBlock), max_work), dim3(256), 0, s, f);
+      hipLaunchKernelGGL(ffn_gateup_mfma, dim3(inter / (kGateUpJ * kWavesPerBlock), max_work), dim3(256), 0, s, f);
     }
     {
       StageTimer tm(SERE_STAGE_DOWN, s);
-      hipLaunchKernelGGL(ffn_down_mfma, dim3(((c.hidden + kDownRows * kWavesPerBlock - 1) / (kDownRows * kWavesPerBlock)) * l.ksplit, max_work), dim3(256), 0, s, f);
+      hipLaunchKernelGGL(ffn_down_mfma,
+                         dim3(((hidden + kDownRows * kWavesPerBlock - 1) / (kDownRows * kWavesPerBlock)) * ksplit,
+                              max_work),
+                         dim3(256), 0, s, f);
     }
   }
+}
+
+static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
+                       hipStream_t s) {
+  launch_gateup_down(c.dtype, c.inter, c.hidden, l.max_work, l.ksplit, f, s);
   launch_combine(c, l, p, out, s);
 }
+
+// wide experts: h keeps its bf16 rounding residual in a second plane (see decode())
+static int wants_split_h(const sere_config& c) { return (c.dtype == SERE_BF16 && c.inter >= 4096) ? 1 : 0; }
 
 static int decode(const sere_config* cfg, const void* hidden, const void* router_w, const void* w_gate_up,
                   const void* w_down, const void* shared_gate_up, const void* shared_down, const float* sim,
@@ -352,9 +366,44 @@ static int decode(const sere_config* cfg, const void* hidden, const void* router
   // tolerance for narrow experts, but not for very wide ones whose outputs
   // reach several units.  From d_m = 4096 on, h keeps its rounding residual in
   // a second bf16 plane and the down projection multiplies both.
-  f.split_h = (cfg->dtype == SERE_BF16 && cfg->inter >= 4096) ? 1 : 0;
+  f.split_h = wants_split_h(*cfg);
   launch_ffn(*cfg, l, p, f, out, s);
   return hip_status();
+}
+
+// ------------------------------------------------------------- similarity ---
+struct SimLayout {
+  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, total;
+  int rows, ksplit;
+};
+
+static SimLayout make_sim_layout(const sere_config& c, int n) {
+  SimLayout l{};
+  const size_t M = c.num_experts, R = M * static_cast<size_t>(n);
+  l.rows = static_cast<int>(R);
+  l.ksplit = down_ksplit(c);
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + bytes);
+    return at;
+  };
+  l.sorted_token = take(R * 4);
+  l.work_expert = take(M * 4);
+  l.work_off = take(M * 4);
+  l.work_cnt = take(M * 4);
+  l.n_work = take(4);
+  l.h = take(R * c.inter * sizeof(float));
+  l.y = take(static_cast<size_t>(l.ksplit) * R * c.hidden * sizeof(float));
+  l.dist = take(M * M * sizeof(double));
+  l.acc = take(M * M * sizeof(double));
+  l.total = o;
+  return l;
+}
+
+static int check_similarity_sizes(int32_t num_batches, int32_t n) {
+  if (num_batches < 1 || num_batches > 4096 || n < 1 || n > 4096) return SERE_ERR_BAD_SHAPE;
+  return SERE_OK;
 }
 
 }  // namespace sere
@@ -428,6 +477,68 @@ int sere_moe_decode_baseline(const sere_config* cfg, const void* hidden, const v
                              size_t workspace_bytes, void* hip_stream) {
   return decode(cfg, hidden, router_w, w_gate_up, w_down, shared_gate_up, shared_down, nullptr, out, dbg,
                 workspace, workspace_bytes, hip_stream, false);
+}
+
+size_t sere_similarity_workspace_bytes(const sere_config* cfg, int32_t batch_tokens) {
+  if (check_config(cfg) != SERE_OK || check_similarity_sizes(1, batch_tokens) != SERE_OK) return 0;
+  return make_sim_layout(*cfg, batch_tokens).total;
+}
+
+int sere_similarity(const sere_config* cfg, const void* calib, int32_t num_batches, int32_t batch_tokens,
+                    const void* w_gate_up, const void* w_down, float* sim, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != SERE_OK) return st;
+  st = check_similarity_sizes(num_batches, batch_tokens);
+  if (st != SERE_OK) return st;
+  PtrCheck pc;
+  pc.need(calib);
+  pc.need(w_gate_up);
+  pc.need(w_down);
+  pc.need(sim);
+  if (pc.status != SERE_OK) return pc.status;
+  const SimLayout l = make_sim_layout(*cfg, batch_tokens);
+  if (workspace == nullptr) return SERE_ERR_NULL_PTR;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SERE_ERR_MISALIGNED;
+  if (workspace_bytes < l.total) return SERE_ERR_WORKSPACE_TOO_SMALL;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  const int M = cfg->num_experts, n = batch_tokens;
+  FfnArgs f{};
+  f.w_gate_up = w_gate_up;
+  f.w_down = w_down;
+  f.sorted_token = reinterpret_cast<int32_t*>(ws + l.sorted_token);
+  f.work_expert = reinterpret_cast<int32_t*>(ws + l.work_expert);
+  f.work_off = reinterpret_cast<int32_t*>(ws + l.work_off);
+  f.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
+  f.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
+  f.h = reinterpret_cast<float*>(ws + l.h);
+  f.y = reinterpret_cast<float*>(ws + l.y);
+  f.T = n;
+  f.dh = cfg->hidden;
+  f.dm = cfg->inter;
+  f.M = M;
+  f.K = 1;
+  f.n_sh = 0;
+  f.ksplit = l.ksplit;
+  f.rows = l.rows;
+  f.split_h = wants_split_h(*cfg);
+  hipLaunchKernelGGL(similarity_worklist_kernel, dim3((M * n + 255) / 256), dim3(256), 0, s, M, n,
+                     const_cast<int32_t*>(f.sorted_token), const_cast<int32_t*>(f.work_expert),
+                     const_cast<int32_t*>(f.work_off), const_cast<int32_t*>(f.work_cnt),
+                     const_cast<int32_t*>(f.n_work));
+  const size_t eb = cfg->dtype == SERE_F32 ? 4 : 2;
+  for (int b = 0; b < num_batches; ++b) {
+    f.hidden = static_cast<const char*>(calib) + static_cast<size_t>(b) * n * cfg->hidden * eb;
+    launch_gateup_down(cfg->dtype, cfg->inter, cfg->hidden, M, l.ksplit, f, s);
+    hipLaunchKernelGGL(pair_distance_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, M,
+                       reinterpret_cast<double*>(ws + l.dist));
+    hipLaunchKernelGGL(similarity_accumulate_kernel, dim3(1), dim3(1024), 0, s,
+                       reinterpret_cast<const double*>(ws + l.dist), M, b, num_batches,
+                       reinterpret_cast<double*>(ws + l.acc), sim);
+  }
+  return hip_status();
 }
 
 int sere_stage_timing(int enable) {

@@ -34,6 +34,25 @@ def to_host(t, dtype: int) -> np.ndarray:
     return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+def similarity_on_device(wl: Workload, weights=None, device="cuda"):
+    """Expert-similarity matrix of the workload's layer from its calibration
+    tokens, computed by the library (sere_similarity); returns a device fp32 [M, M]
+    tensor.  `weights` = (router_w, w_gate_up, w_down, ...) already on the device."""
+    import torch
+    sp = wl.spec
+    n_batches, n_tokens = wl.calib.shape[0], wl.calib.shape[1]
+    cfg = B.make_config(n_tokens, sp.hidden, sp.experts, min(sp.top_k, sp.experts), sp.inter, 0,
+                        sp.dtype, 1, 0.0)
+    gu = to_device(wl.w_gate_up, sp.dtype, device) if weights is None else weights[1]
+    dn = to_device(wl.w_down, sp.dtype, device) if weights is None else weights[2]
+    calib = to_device(wl.calib, sp.dtype, device)
+    sim = torch.empty((sp.experts, sp.experts), dtype=torch.float32, device=device)
+    ws = torch.empty(B.sere_similarity_workspace_bytes(cfg, n_tokens), dtype=torch.uint8, device=device)
+    B.sere_similarity(cfg, calib, n_batches, n_tokens, gu, dn, sim, ws)
+    torch.cuda.synchronize()
+    return sim
+
+
 @dataclass
 class DeviceLayer:
     """One MoE layer's tensors resident in HBM plus the call-time buffers."""
@@ -65,9 +84,10 @@ class DeviceLayer:
                        to_device(wl.shared_gate_up, sp.dtype, device),
                        to_device(wl.shared_down, sp.dtype, device))
         tdt = torch.float32 if sp.dtype == F32 else torch.bfloat16
+        if isinstance(sim, np.ndarray):
+            sim = torch.from_numpy(np.ascontiguousarray(sim, dtype=np.float32)).to(device)
         return DeviceLayer(
-            sp, to_device(wl.hidden, sp.dtype, device), *weights,
-            torch.from_numpy(np.ascontiguousarray(sim, dtype=np.float32)).to(device),
+            sp, to_device(wl.hidden, sp.dtype, device), *weights, sim,
             torch.zeros((wl.hidden.shape[0], sp.hidden), dtype=tdt, device=device),
             B.alloc_workspace(cfg, device), B.RouteBuffers.allocate(cfg, device), cfg)
 

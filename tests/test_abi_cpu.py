@@ -20,8 +20,8 @@ def declared_functions():
 def test_exports_every_declared_symbol():
     lib = B.load()
     names = declared_functions()
-    assert {"sere_route", "sere_moe_decode", "sere_moe_decode_baseline", "sere_reroute",
-            "sere_workspace_bytes", "sere_status_string"} <= set(names)
+    assert {"sere_route", "sere_moe_decode", "sere_moe_decode_baseline", "sere_reroute", "sere_similarity",
+            "sere_workspace_bytes", "sere_similarity_workspace_bytes", "sere_status_string"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"libsere.so does not export {n}"
 
@@ -103,6 +103,21 @@ def test_bad_pointers_rejected():
     o.count_after = FAKE + 2
     assert lib.sere_route(ctypes.byref(good()), FAKE, FAKE, FAKE, ctypes.byref(o), FAKE, 1 << 40,
                           None) == B.SERE_ERR_MISALIGNED
+
+
+def test_similarity_validation():
+    lib = B.load()
+    cfg = good()
+    c = ctypes.byref(cfg)
+    assert B.sere_similarity_workspace_bytes(cfg, 32) > 0
+    assert B.sere_similarity_workspace_bytes(cfg, 0) == 0
+    assert lib.sere_similarity(c, FAKE, 0, 32, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == B.SERE_ERR_BAD_SHAPE
+    assert lib.sere_similarity(c, FAKE, 2, 5000, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == B.SERE_ERR_BAD_SHAPE
+    assert lib.sere_similarity(c, None, 2, 32, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == B.SERE_ERR_NULL_PTR
+    assert lib.sere_similarity(c, FAKE, 2, 32, FAKE, FAKE, FAKE + 8, FAKE, 1 << 40, None) == B.SERE_ERR_MISALIGNED
+    assert lib.sere_similarity(c, FAKE, 2, 32, FAKE, FAKE, FAKE, FAKE, 16, None) == B.SERE_ERR_WORKSPACE_TOO_SMALL
+    cfg.dtype = 7
+    assert lib.sere_similarity(c, FAKE, 2, 32, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == B.SERE_ERR_BAD_DTYPE
 
 
 def test_binding_raises_on_error():

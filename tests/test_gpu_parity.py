@@ -328,3 +328,39 @@ def test_stage_timing_reports_every_stage(dev):
     B.sere_stage_timing(False)
     assert all(n[s] == 3 for s in B.STAGES), n
     assert all(ms[s] > 0 for s in B.STAGES), ms
+
+
+# ------------------------------------------------------- similarity matrix ---
+@pytest.mark.parametrize("name", ["tiny", "qwen3_b32", "mixtral_b64"])
+def test_similarity_parity(dev, name):
+    """sere_similarity (all-expert forward + pairwise Frobenius distances on the
+    GPU) against the oracle's fp64 estimate.  The bf16 path carries bf16-level
+    rounding in the activations, hence the tolerance: distances are relative
+    2^-9-ish, similarities 1 - x/max move by at most a few 1e-3."""
+    wl, layer, sim_ref = device_layer(dev, name)
+    print(f"similarity {name}", flush=True)
+    got = dev.similarity_on_device(wl, layer.weights()).cpu().numpy()
+    tol = 1e-5 if wl.spec.dtype == wk.F32 else 5e-3
+    assert got.shape == sim_ref.shape
+    assert np.abs(got - sim_ref).max() <= tol, np.abs(got - sim_ref).max()
+    assert np.allclose(got, got.T, atol=1e-6)
+    assert np.allclose(np.diag(got), 1.0, atol=1e-6)
+    assert got.min() >= -1e-6 and got.max() <= 1.0 + 1e-6
+    sp = wl.spec
+    for i in range(sp.twin_n):          # planted twins stay each other's nearest expert
+        a, b = sp.twin_src + i, sp.twin_dst + i
+        row = got[a].copy(); row[a] = -1
+        assert int(np.argmax(row)) == b
+
+
+def test_similarity_feeds_routing(dev):
+    """The library's own similarity matrix drives the same re-routing as the
+    oracle's on the tiny fp32 layer (values agree to 1e-5 and no two candidate
+    similarities are that close)."""
+    wl, layer, sim_ref = device_layer(dev, "tiny")
+    sim_gpu = dev.similarity_on_device(wl, layer.weights())
+    mine = dev.DeviceLayer.from_workload(wl, sim_gpu, 1, 0.0, weights=layer.weights())
+    mine.run_route()
+    got = mine.routing_to_host()
+    ref = oracle_route(wl, sim_ref, 1, 0.0, "tiny")
+    assert np.array_equal(got["rerouted_ids"], ref.rerouted_ids)
