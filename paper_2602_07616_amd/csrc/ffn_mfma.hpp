@@ -291,7 +291,7 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W
 }
 
 // grid (dm / 32, M + n_sh), 256 threads: 4 wavefronts x 8 intermediate indices
-__global__ __launch_bounds__(256) void ffn_gateup_mfma(FfnArgs p) {
+__global__ __launch_bounds__(256, 4) void ffn_gateup_mfma(FfnArgs p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
   const int w = blockIdx.y;
   if (w >= *p.n_work) return;
@@ -347,7 +347,7 @@ __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, 
 }
 
 // grid (ceil(dh / 128) * ksplit, M + n_sh), 256 threads: 4 wavefronts x 32 output rows
-__global__ __launch_bounds__(256) void ffn_down_mfma(FfnArgs p) {
+__global__ __launch_bounds__(256, 4) void ffn_down_mfma(FfnArgs p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
   const int w = blockIdx.y;
   if (w >= *p.n_work) return;

@@ -364,3 +364,46 @@ def test_similarity_feeds_routing(dev):
     got = mine.routing_to_host()
     ref = oracle_route(wl, sim_ref, 1, 0.0, "tiny")
     assert np.array_equal(got["rerouted_ids"], ref.rerouted_ids)
+
+
+# ------------------------------------------- the launch shape bench.py times ---
+def test_graph_replay_matches_eager_and_oracle(dev):
+    """bench.py replays a HIP graph that holds one decode step per weight copy.
+    Capture two steps (two copies of the Qwen3-shaped layer) into a graph, replay
+    it several times with eager work and synchronisations in between, and check
+    every replay bit for bit against the eager result and (on sampled tokens)
+    within tolerance against the oracle."""
+    import torch
+    wl, layer, sim = device_layer(dev, "qwen3_b32")
+    copy = dev.DeviceLayer.from_workload(
+        wl, sim, 2, 0.0, weights=tuple(None if t is None else t.clone() for t in layer.weights()))
+    layers = [layer, copy]
+    for l in layers:
+        l.set_knobs(2, 0.0)
+        l.out.zero_()
+        l.run_decode(with_outputs=False)
+    torch.cuda.synchronize()
+    eager = [l.out.clone() for l in layers]
+    assert (eager[0] == eager[1]).all()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        for l in layers:
+            l.run_decode(stream, with_outputs=False)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            for l in layers:
+                l.run_decode(stream, with_outputs=False)
+    for rep in range(4):
+        for l in layers:
+            l.out.fill_(7.0)                 # eager work between replays
+            l.workspace.fill_(0x33)          # stale scratch must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l, e in zip(layers, eager):
+            assert (l.out == e).all(), f"replay {rep}"
+    ref = oracle_route(wl, sim, 2, 0.0, "qwen3_b32")
+    tokens = [0, 5, 11, 17, 23, 31]
+    want = oracle_output(wl, ref.rerouted_ids, ref.topk_weights, "qwen3_b32", tokens)
+    check_output(layers[1].out_to_host_f64()[tokens], want, wl.spec.dtype, "graph replay")
