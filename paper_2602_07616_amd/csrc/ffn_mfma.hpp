@@ -69,8 +69,19 @@ __device__ __forceinline__ u32x4 lower_from(u32x4 keep, u32x4 other) {
 }
 
 constexpr int kTile = 16;      // tokens per MFMA tile
-constexpr int kGateUpJ = 8;    // intermediate indices per wavefront (8 gate rows + 8 up rows = one tile)
-constexpr int kDownRows = 32;  // output rows per wavefront (two tiles)
+// Work per workgroup: two cuts.  With few work items the grid is only a few workgroups per
+// compute unit and one workgroup more on some compute units decides the kernel time, so the
+// items are cut fine (half the weight rows per workgroup, twice the workgroups).  With many
+// items the coarse cut wins: the token tile is staged into LDS once per workgroup, which per
+// weight byte costs half as much there.  The routing step chooses per call (n_work[1]); the
+// grid is sized for the fine cut; under the coarse cut the workgroups are renumbered along
+// their linear id, so that those with work come first and the idle ones (about half) sit
+// at the end of the grid, where they cost nothing but their launch.
+constexpr int kGateUpJ = 4;    // intermediate indices per wavefront, fine cut: 4 gate + 4 up rows = the
+                               // upper half of one tile (coarse: 8 + 8 = one tile)
+constexpr int kDownRows = 16;  // output rows per wavefront, fine cut: one tile (coarse: two tiles)
+constexpr int kFineCutBlocks = 2560;  // fine cut while the coarse gate/up grid would hold at most this many
+                                      // working workgroups (ten per compute unit)
 constexpr int kWavesPerBlock = 4;
 
 // The token operand (hidden states for gate/up, h for down) is shared by the
@@ -111,7 +122,7 @@ struct TokenSource {
 //   lo_plane     : with LO, a second token operand `lo_plane` elements after the
 //                  first is multiplied too (token = high + low bf16 parts)
 // All 256 threads of the workgroup must call this together (it has barriers).
-template <int NA, int NT, int KC, bool LO>
+template <int NA, int NT, int KC, bool LO, bool HALF = false>
 __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], const uint16_t* const (&wy)[NA],
                                              const TokenSource& tok, size_t lo_plane, int kbeg, int kend, int rot,
                                              unsigned char* lds, f32x4 (&acc)[NA][NT]) {
@@ -170,7 +181,7 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
         x[a][b - b0] = load_weight(wx[a] + kk);
-        y[a][b - b0] = load_weight(wy[a] + kk);
+        if (!HALF) y[a][b - b0] = load_weight(wy[a] + kk);
       }
     }
   };
@@ -190,8 +201,9 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
           }
 #pragma unroll
         for (int a = 0; a < NA; ++a) {
-          const u32x4 a_even = upper_from(x[a][b - b0], y[a][b - b0]);
-          const u32x4 a_odd = lower_from(y[a][b - b0], x[a][b - b0]);
+          // HALF: the tile's rows 8-15 are not used; they multiply whatever the lanes hold
+          const u32x4 a_even = HALF ? x[a][b - b0] : upper_from(x[a][b - b0], y[a][b - b0]);
+          const u32x4 a_odd = HALF ? lower_from(x[a][b - b0], x[a][b - b0]) : lower_from(y[a][b - b0], x[a][b - b0]);
 #pragma unroll
           for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
@@ -230,6 +242,18 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
   __syncthreads();  // the LDS buffers may be refilled by the caller's next group
 }
 
+// Which (work item, part of the item) this workgroup serves.  Fine cut: (blockIdx.y,
+// blockIdx.x).  Coarse cut: an item has coarse_parts parts, numbered along the linear
+// workgroup id.
+struct BlockMap {
+  int item, part;
+};
+__device__ __forceinline__ BlockMap map_block(bool fine, int coarse_parts) {
+  if (fine) return BlockMap{static_cast<int>(blockIdx.y), static_cast<int>(blockIdx.x)};
+  const unsigned id = blockIdx.y * gridDim.x + blockIdx.x;
+  return BlockMap{static_cast<int>(id / coarse_parts), static_cast<int>(id % coarse_parts)};
+}
+
 // first chunk of a workgroup: spread over the row
 __device__ __forceinline__ int start_rotation(int len, int chunk) {
   const int n = (len + chunk - 1) / chunk;
@@ -246,29 +270,33 @@ __device__ __forceinline__ int start_rotation(int len, int chunk) {
 // h = silu(gate) * up is stored as bf16 (plus, if split_h, the bf16 rounding
 // residual in a second plane).
 // ---------------------------------------------------------------------------
-template <int NT, int KC>
+template <int NT, int KC, bool HALF>
 __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W, int j0, int row0, int nrows,
                                              unsigned char* lds) {
   const int lane = threadIdx.x & 63;
   const int i = lane & 15, g = lane >> 4;
   const int dh = p.dh, dm = p.dm;
   const int chunk = 2 * g + (i >> 3);
-  const uint16_t* wx[1] = {W + static_cast<size_t>(j0 + (i & 7)) * dh + 8 * chunk};
+  // HALF: the one half tile holds gate rows j0..j0+3 (tile rows 0-3) and up rows (tile rows 4-7)
+  const int xrow = HALF ? ((i & 4) ? dm + j0 + (i & 3) : j0 + (i & 3)) : j0 + (i & 7);
+  const uint16_t* wx[1] = {W + static_cast<size_t>(xrow) * dh + 8 * chunk};
   const uint16_t* wy[1] = {W + static_cast<size_t>(dm + j0 + (i & 7)) * dh + 8 * chunk};
   const TokenSource tok{static_cast<const uint16_t*>(p.hidden), p.sorted_token, row0, nrows, dh};
   f32x4 acc[1][NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[0][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tiles<1, NT, KC, false>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC), lds, acc);
+  stream_tiles<1, NT, KC, false, HALF>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC), lds, acc);
 
+  // gate values sit in lanes g < GL, the up values of the same (j, token) GL * 16 lanes higher
+  constexpr int GL = HALF ? 1 : 2;
   uint16_t* h = reinterpret_cast<uint16_t*>(p.h);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     f32x4 up;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) up[r] = __shfl(acc[0][t][r], (lane + 32) & 63, kWave);
+    for (int r = 0; r < 4; ++r) up[r] = __shfl(acc[0][t][r], (lane + 16 * GL) & 63, kWave);
     const int n = t * kTile + i;
-    if (g < 2 && n < nrows) {
+    if (g < GL && n < nrows) {
       uint16_t hi[4], lo[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -290,21 +318,34 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W
   }
 }
 
-// grid (dm / 32, M + n_sh), 256 threads: 4 wavefronts x 8 intermediate indices
+// grid (dm / 16, max items), 256 threads: 4 wavefronts x 4 (fine) or 8 (coarse) intermediate indices
 __global__ __launch_bounds__(256, 4) void ffn_gateup_mfma(FfnArgs p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
-  const int w = blockIdx.y;
-  if (w >= *p.n_work) return;
+  const int2 nw = *reinterpret_cast<const int2*>(p.n_work);  // items, fine cut?
+  const bool fine = nw.y != 0;
+  const BlockMap at = map_block(fine, gridDim.x / 2);
+  const int w = at.item;
+  if (w >= nw.x) return;
   const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
   const uint16_t* W = static_cast<const uint16_t*>(
       expert_base<SERE_BF16>(p.w_gate_up, p.shared_gate_up, e, p.M, static_cast<size_t>(2) * p.dm * p.dh));
-  const int j0 = (blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kGateUpJ;
+  const int wave = threadIdx.x >> 6;
   // the routing step cuts experts into items of at most 32 rows; longer items (the
   // similarity estimation's) are served 32 rows at a time, streaming the weights again
-  if (cnt <= kTile) {
-    gateup_group<1, 256>(p, W, j0, off, cnt, lds);
+  if (fine) {
+    const int j0 = (at.part * kWavesPerBlock + wave) * kGateUpJ;
+    if (cnt <= kTile) {
+      gateup_group<1, 512, true>(p, W, j0, off, cnt, lds);
+    } else {
+      for (int q = 0; q < cnt; q += 2 * kTile) gateup_group<2, 256, true>(p, W, j0, off + q, min(2 * kTile, cnt - q), lds);
+    }
   } else {
-    for (int q = 0; q < cnt; q += 2 * kTile) gateup_group<2, 256>(p, W, j0, off + q, min(2 * kTile, cnt - q), lds);
+    const int j0 = (at.part * kWavesPerBlock + wave) * (2 * kGateUpJ);
+    if (cnt <= kTile) {
+      gateup_group<1, 256, false>(p, W, j0, off, cnt, lds);
+    } else {
+      for (int q = 0; q < cnt; q += 2 * kTile) gateup_group<2, 256, false>(p, W, j0, off + q, min(2 * kTile, cnt - q), lds);
+    }
   }
 }
 
@@ -314,7 +355,7 @@ __global__ __launch_bounds__(256, 4) void ffn_gateup_mfma(FfnArgs p) {
 // operand is h_hi + h_lo (two MFMAs per weight fragment).  Partial results go
 // to y[slice][row][r] (fp32).
 // ---------------------------------------------------------------------------
-template <int NT, int KC, bool LO>
+template <int NA, int NT, int KC, bool LO>
 __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, int r0, int kbeg, int kend,
                                            int slice, int row0, int nrows, unsigned char* lds) {
   const int lane = threadIdx.x & 63;
@@ -325,13 +366,20 @@ __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, 
   // still takes part in the staging; those wavefronts stream row block 0 again and store nothing
   const bool live = r0 < dh;
   const uint16_t* base = W + static_cast<size_t>((live ? r0 : 0) + (i & 7)) * dm + 8 * chunk;
-  const uint16_t* wx[2] = {base, base + static_cast<size_t>(16) * dm};
-  const uint16_t* wy[2] = {base + static_cast<size_t>(8) * dm, base + static_cast<size_t>(24) * dm};
-  const TokenSource tok{reinterpret_cast<const uint16_t*>(p.h), nullptr, row0, nrows, dm};
-  f32x4 acc[2][NT];
+  const uint16_t* wx[NA];
+  const uint16_t* wy[NA];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) acc[0][t] = acc[1][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tiles<2, NT, KC, LO>(wx, wy, tok, static_cast<size_t>(p.rows) * dm, kbeg, kend,
+  for (int a = 0; a < NA; ++a) {
+    wx[a] = base + static_cast<size_t>(16 * a) * dm;
+    wy[a] = base + static_cast<size_t>(16 * a + 8) * dm;
+  }
+  const TokenSource tok{reinterpret_cast<const uint16_t*>(p.h), nullptr, row0, nrows, dm};
+  f32x4 acc[NA][NT];
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  stream_tiles<NA, NT, KC, LO>(wx, wy, tok, static_cast<size_t>(p.rows) * dm, kbeg, kend,
                               start_rotation(kend - kbeg, KC), lds, acc);
   if (!live) return;
   float* y = p.y + static_cast<size_t>(slice) * p.rows * dh;
@@ -340,37 +388,63 @@ __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, 
     const int n = t * kTile + i;
     if (n < nrows) {
       float* dst = y + static_cast<size_t>(row0 + n) * dh + r0 + 4 * g;
-      *reinterpret_cast<f32x4*>(dst) = acc[0][t];
-      *reinterpret_cast<f32x4*>(dst + 16) = acc[1][t];
+#pragma unroll
+      for (int a = 0; a < NA; ++a) *reinterpret_cast<f32x4*>(dst + 16 * a) = acc[a][t];
     }
   }
 }
 
-// grid (ceil(dh / 128) * ksplit, M + n_sh), 256 threads: 4 wavefronts x 32 output rows
+// grid (ceil(dh / 64) * ksplit, max items), 256 threads: 4 wavefronts x 16 (fine) or 32 (coarse) output rows
 __global__ __launch_bounds__(256, 4) void ffn_down_mfma(FfnArgs p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
-  const int w = blockIdx.y;
-  if (w >= *p.n_work) return;
+  const int2 nw = *reinterpret_cast<const int2*>(p.n_work);  // items, fine cut?
+  const bool fine = nw.y != 0;
+  const int coarse_slabs = (p.dh + 2 * kDownRows * kWavesPerBlock - 1) / (2 * kDownRows * kWavesPerBlock);
+  const BlockMap at = map_block(fine, coarse_slabs * p.ksplit);
+  const int w = at.item;
+  if (w >= nw.x) return;
   const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
   const uint16_t* W = static_cast<const uint16_t*>(
       expert_base<SERE_BF16>(p.w_down, p.shared_down, e, p.M, static_cast<size_t>(p.dh) * p.dm));
-  const int slab = blockIdx.x / p.ksplit, slice = blockIdx.x % p.ksplit;
-  const int r0 = (slab * kWavesPerBlock + (threadIdx.x >> 6)) * kDownRows;
+  const int slab = at.part / p.ksplit, slice = at.part % p.ksplit;
+  const int wave = threadIdx.x >> 6;
   // this slice of d_m, in 64-wide blocks
   const int blocks = p.dm >> 6, per = (blocks + p.ksplit - 1) / p.ksplit;
   const int kbeg = min(slice * per, blocks) << 6, kend = min((slice + 1) * per, blocks) << 6;
-  if (p.split_h) {
+  if (fine) {
+    const int r0 = (slab * kWavesPerBlock + wave) * kDownRows;
     if (cnt <= kTile) {
-      down_group<1, 128, true>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
+      if (p.split_h) {
+        down_group<1, 1, 256, true>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
+      } else {
+        down_group<1, 1, 256, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
+      }
     } else {
-      for (int q = 0; q < cnt; q += 2 * kTile)
-        down_group<2, 64, true>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
+      for (int q = 0; q < cnt; q += 2 * kTile) {
+        if (p.split_h) {
+          down_group<1, 2, 64, true>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
+        } else {
+          down_group<1, 2, 256, false>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
+        }
+      }
     }
-  } else if (cnt <= kTile) {
-    down_group<1, 128, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
   } else {
-    for (int q = 0; q < cnt; q += 2 * kTile)
-      down_group<2, 128, false>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
+    const int r0 = (slab * kWavesPerBlock + wave) * (2 * kDownRows);
+    if (cnt <= kTile) {
+      if (p.split_h) {
+        down_group<2, 1, 128, true>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
+      } else {
+        down_group<2, 1, 128, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
+      }
+    } else {
+      for (int q = 0; q < cnt; q += 2 * kTile) {
+        if (p.split_h) {
+          down_group<2, 2, 64, true>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
+        } else {
+          down_group<2, 2, 128, false>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
+        }
+      }
+    }
   }
 }
 

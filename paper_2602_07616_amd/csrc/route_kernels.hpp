@@ -290,7 +290,8 @@ struct RouteArgs {
                             //             ascending, an expert's rows cut into items of <= kItemRows
   int32_t* work_off;        // [max items] first row of the item in the sorted list
   int32_t* work_cnt;        // [max items] rows of the item (1 .. kItemRows)
-  int32_t* n_work;          // [1]
+  int32_t* n_work;          // [2]: number of items; 1 if the FFN kernels are to cut them fine
+  int fine_items;           // ... which they do while there are at most this many items
 };
 
 constexpr int kRouteThreads = 1024;
@@ -484,6 +485,7 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
     p.num_active[0] = n_before;
     p.num_active[1] = n_after;
     p.n_work[0] = n_items + p.n_sh * sh_items;
+    p.n_work[1] = n_items + p.n_sh * sh_items <= p.fine_items ? 1 : 0;
   }
   for (int i = tid; i < p.n_sh * sh_items; i += kRouteThreads) {
     const int sh = i / sh_items, j = i % sh_items;

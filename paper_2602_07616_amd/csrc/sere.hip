@@ -63,7 +63,7 @@ static Layout make_layout(const sere_config& c) {
   l.work_expert = take(W * 4);
   l.work_off = take(W * 4);
   l.work_cnt = take(W * 4);
-  l.n_work = take(4);
+  l.n_work = take(8);
   l.ticket = take(4);
   l.h = take(R * c.inter * sizeof(float));
   l.y = take(static_cast<size_t>(l.ksplit) * R * c.hidden * sizeof(float));
@@ -206,6 +206,7 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
   r.work_off = reinterpret_cast<int32_t*>(ws + l.work_off);
   r.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
   r.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
+  r.fine_items = kFineCutBlocks / (c.inter / (2 * kGateUpJ * kWavesPerBlock));
   p.h = reinterpret_cast<float*>(ws + l.h);
   p.y = reinterpret_cast<float*>(ws + l.y);
   return p;
@@ -392,7 +393,7 @@ static SimLayout make_sim_layout(const sere_config& c, int n) {
   l.work_expert = take(M * 4);
   l.work_off = take(M * 4);
   l.work_cnt = take(M * 4);
-  l.n_work = take(4);
+  l.n_work = take(8);
   l.h = take(R * c.inter * sizeof(float));
   l.y = take(static_cast<size_t>(l.ksplit) * R * c.hidden * sizeof(float));
   l.dist = take(M * M * sizeof(double));

@@ -21,7 +21,10 @@ __global__ __launch_bounds__(256) void similarity_worklist_kernel(int M, int n, 
     work_off[i] = i * n;
     work_cnt[i] = n;
   }
-  if (i == 0) *n_work = M;
+  if (i == 0) {
+    n_work[0] = M;
+    n_work[1] = 0;  // many long items: coarse cut
+  }
 }
 
 // dist[p][q] = sqrt(sum_i (A_p[i] - A_q[i])^2), A_e = sum over slices of y[slice][e*n .. e*n+n) rows.
