@@ -25,6 +25,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
+# HBM bytes per launch (read + write) of the two FFN kernels, from rocprofv3 --pmc FETCH_SIZE
+# and --pmc WRITE_SIZE runs of `bench.py --only-sere --copy-calibration --no-graph`, each counter
+# scaled by what it reads for the plain 256 MiB copy in the same run (FETCH_SIZE x 1.9998,
+# WRITE_SIZE x 1.0000); commands and tables: profiles/sere_step_<workload>.md.  Keyed by
+# (workload, select_top_k, threshold); other configurations report null.
+MEASURED_TRAFFIC = {
+    ("qwen3_b32", 2, 0.0): {"gate_up": 204660005, "down": 106605993},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -123,7 +132,7 @@ class Runner:
         return total_ms * 1e3 / steps, per_round, wall * 1e6 / steps
 
     def stage_times(self, mode, steps):
-        """Average duration of each kernel stage (HIP events on the launch stream)."""
+        """Average duration of each kernel stage (HIP events attached to each dispatch on the launch stream)."""
         from paper_2602_07616_amd import binding as B
         n = len(self.layers)
         with self.torch.cuda.stream(self.stream):
@@ -226,12 +235,14 @@ def main():
     gateup_bytes = sere["experts_read"] * 2 * spec.hidden * spec.inter * eb
     down_bytes = sere["experts_read"] * spec.hidden * spec.inter * eb
     achieved = gateup_bytes / stages["gate_up"] * 1e-3 if stages["gate_up"] else 0.0
+    traffic = MEASURED_TRAFFIC.get((spec.name, args.S, float(args.rho)), {})
     roofline = {"bound": "hbm", "kernel": "gate_up", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic.get("gate_up"),
                 "algorithmic_bytes_per_launch": gateup_bytes,
                 "avg_launch_us": round(stages["gate_up"], 2),
                 "down": {"achieved": round(down_bytes / stages["down"] * 1e-3, 1) if stages["down"] else 0.0,
-                         "avg_launch_us": round(stages["down"], 2), "algorithmic_bytes_per_launch": down_bytes},
+                         "avg_launch_us": round(stages["down"], 2), "algorithmic_bytes_per_launch": down_bytes,
+                         "traffic": traffic.get("down")},
                 "stage_us": {k: round(v, 2) for k, v in stages.items()}}
 
     result = {

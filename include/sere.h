@@ -199,8 +199,12 @@ int sere_similarity(const sere_config *cfg, const void *calib, int32_t num_batch
 
 /*
  * Per-kernel timing for benchmarks.  While enabled, every kernel the calls
- * above enqueue is bracketed by HIP events on the caller's stream (at most
+ * above enqueue carries a pair of HIP events attached to its own dispatch on
+ * the caller's stream: they take the kernel's start and end time stamps, so
+ * the elapsed time is the kernel's duration as a profiler's kernel trace
+ * reports it, without the gap to its neighbours (at most
  * SERE_TIMING_MAX_RECORDS launches are kept, later ones are not recorded).
+ * Do not enable it on a stream that is being captured into a HIP graph.
  * sere_stage_timing_read waits for the recorded events, adds the elapsed
  * milliseconds and launch counts per stage into the two arrays of
  * SERE_NUM_STAGES entries, and clears the records.  Process-global, not

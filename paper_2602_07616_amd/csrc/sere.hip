@@ -1,5 +1,6 @@
 // Host side of the C ABI declared in include/sere.h: argument validation,
 // workspace layout and kernel launches.  Nothing here synchronises the device.
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -138,29 +139,37 @@ struct Timing {
 };
 static Timing g_timing;
 
-struct StageTimer {
-  hipStream_t stream;
-  bool active = false;
-  StageTimer(int stage, hipStream_t s) : stream(s) {
-    Timing& t = g_timing;
-    if (!t.enabled || t.n >= SERE_TIMING_MAX_RECORDS) return;
-    if (t.n >= t.created) {
-      if (hipEventCreate(&t.start[t.created]) != hipSuccess) return;
-      if (hipEventCreate(&t.stop[t.created]) != hipSuccess) {
-        (void)hipEventDestroy(t.start[t.created]);
-        return;
-      }
-      ++t.created;
+// Event pair for the next launch of `stage`, if timing is on and a record is free.
+static bool timing_slot(int stage, hipEvent_t* start, hipEvent_t* stop) {
+  Timing& t = g_timing;
+  if (!t.enabled || t.n >= SERE_TIMING_MAX_RECORDS) return false;
+  if (t.n >= t.created) {
+    if (hipEventCreate(&t.start[t.created]) != hipSuccess) return false;
+    if (hipEventCreate(&t.stop[t.created]) != hipSuccess) {
+      (void)hipEventDestroy(t.start[t.created]);
+      return false;
     }
-    t.stage[t.n] = stage;
-    active = hipEventRecord(t.start[t.n], stream) == hipSuccess;
+    ++t.created;
   }
-  ~StageTimer() {
-    if (!active) return;
-    Timing& t = g_timing;
-    if (hipEventRecord(t.stop[t.n], stream) == hipSuccess) ++t.n;
+  t.stage[t.n] = stage;
+  *start = t.start[t.n];
+  *stop = t.stop[t.n];
+  return true;
+}
+
+// One kernel launch of a stage.  With timing on, the two events are attached to the dispatch
+// itself (they take the kernel's own start and end time stamps, as a profiler's kernel trace
+// does), not recorded around it on the stream.
+template <typename Kernel, typename... Args>
+static void launch_stage(int stage, hipStream_t s, Kernel kernel, dim3 grid, dim3 block, Args... args) {
+  hipEvent_t e0, e1;
+  if (timing_slot(stage, &e0, &e1)) {
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+    ++g_timing.n;
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
   }
-};
+}
 
 // --------------------------------------------------------------- launches ---
 struct Pointers {
@@ -216,86 +225,68 @@ static int hip_status() { return hipGetLastError() == hipSuccess ? SERE_OK : SER
 
 static int launch_router(const sere_config& c, const Pointers& p, const void* hidden,
                          const void* router_w, hipStream_t s) {
-  {
-    StageTimer tm(SERE_STAGE_ROUTER, s);
-    dim3 grid((c.num_experts + 15) / 16, c.num_tokens);
-    if (c.dtype == SERE_F32)
-      hipLaunchKernelGGL(router_logits_kernel<SERE_F32>, grid, dim3(256), 0, s, hidden, router_w, p.list_key,
-                         p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
-    else
-      hipLaunchKernelGGL(router_logits_kernel<SERE_BF16>, grid, dim3(256), 0, s, hidden, router_w, p.list_key,
-                         p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
-  }
+  const dim3 grid((c.num_experts + 15) / 16, c.num_tokens);
+  if (c.dtype == SERE_F32)
+    launch_stage(SERE_STAGE_ROUTER, s, router_logits_kernel<SERE_F32>, grid, dim3(256), hidden, router_w, p.list_key,
+                 p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
+  else
+    launch_stage(SERE_STAGE_ROUTER, s, router_logits_kernel<SERE_BF16>, grid, dim3(256), hidden, router_w,
+                 p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
   return hip_status();
 }
 
 static int launch_route(const sere_config& c, const Pointers& p, bool with_topk, hipStream_t s,
                         const sere_route_out* o, size_t sorted_token_bytes) {
-  {
-    StageTimer tm(SERE_STAGE_ROUTE, s);
-    if (with_topk) {
-      // lanes per token = lists per token rounded up to 4, 8 or 16; K <= KS * lanes
-      const int lists = (c.num_experts + 15) / 16;
-      const int lp = lists <= 4 ? 4 : (lists <= 8 ? 8 : 16);
-      const bool small_k = c.top_k <= 2 * lp;
-      const dim3 grid((c.num_tokens * lp + kRouteThreads - 1) / kRouteThreads);
-#define SERE_LAUNCH_TOPK(LP, KS)                                                                              \
-  hipLaunchKernelGGL((topk_route_kernel<LP, KS>), grid, dim3(kRouteThreads), 0, s, p.list_key, p.list_id, \
-                     p.topk_ids, p.topk_w, p.ticket, p.route)
-      if (lp == 4) {
-        if (small_k) SERE_LAUNCH_TOPK(4, 2); else SERE_LAUNCH_TOPK(4, 16);
-      } else if (lp == 8) {
-        if (small_k) SERE_LAUNCH_TOPK(8, 2); else SERE_LAUNCH_TOPK(8, 16);
-      } else {
-        if (small_k) SERE_LAUNCH_TOPK(16, 2); else SERE_LAUNCH_TOPK(16, 16);
-      }
+  if (with_topk) {
+    // lanes per token = lists per token rounded up to 4, 8 or 16; K <= KS * lanes
+    const int lists = (c.num_experts + 15) / 16;
+    const int lp = lists <= 4 ? 4 : (lists <= 8 ? 8 : 16);
+    const bool small_k = c.top_k <= 2 * lp;
+    const dim3 grid((c.num_tokens * lp + kRouteThreads - 1) / kRouteThreads);
+#define SERE_LAUNCH_TOPK(LP, KS)                                                                                \
+  launch_stage(SERE_STAGE_ROUTE, s, topk_route_kernel<LP, KS>, grid, dim3(kRouteThreads), p.list_key, p.list_id, \
+               p.topk_ids, p.topk_w, p.ticket, p.route)
+    if (lp == 4) {
+      if (small_k) SERE_LAUNCH_TOPK(4, 2); else SERE_LAUNCH_TOPK(4, 16);
+    } else if (lp == 8) {
+      if (small_k) SERE_LAUNCH_TOPK(8, 2); else SERE_LAUNCH_TOPK(8, 16);
+    } else {
+      if (small_k) SERE_LAUNCH_TOPK(16, 2); else SERE_LAUNCH_TOPK(16, 16);
+    }
 #undef SERE_LAUNCH_TOPK
-    } else
-      hipLaunchKernelGGL(route_kernel, dim3(1), dim3(kRouteThreads), 0, s, p.route);
-    // the internal sorted_token list also carries the shared experts' rows; a
-    // caller-visible copy holds the routed part only
-    if (o != nullptr && o->sorted_token != nullptr)
-      (void)hipMemcpyAsync(o->sorted_token, p.route.sorted_token, sorted_token_bytes, hipMemcpyDeviceToDevice, s);
+  } else {
+    launch_stage(SERE_STAGE_ROUTE, s, route_kernel, dim3(1), dim3(kRouteThreads), p.route);
   }
+  // the internal sorted_token list also carries the shared experts' rows; a
+  // caller-visible copy holds the routed part only
+  if (o != nullptr && o->sorted_token != nullptr)
+    (void)hipMemcpyAsync(o->sorted_token, p.route.sorted_token, sorted_token_bytes, hipMemcpyDeviceToDevice, s);
   return hip_status();
 }
 
 static void launch_combine(const sere_config& c, const Layout& l, const Pointers& p, void* out, hipStream_t s) {
-  StageTimer tm(SERE_STAGE_COMBINE, s);
   CombineArgs ca{p.y, p.topk_w, p.route.slot_pos, out, c.num_tokens, c.hidden, c.top_k, c.num_shared, l.ksplit, l.rows};
   const dim3 grid((c.hidden + 255) / 256, c.num_tokens);
   if (c.dtype == SERE_F32)
-    hipLaunchKernelGGL(combine_kernel<SERE_F32>, grid, dim3(256), 0, s, ca);
+    launch_stage(SERE_STAGE_COMBINE, s, combine_kernel<SERE_F32>, grid, dim3(256), ca);
   else
-    hipLaunchKernelGGL(combine_kernel<SERE_BF16>, grid, dim3(256), 0, s, ca);
+    launch_stage(SERE_STAGE_COMBINE, s, combine_kernel<SERE_BF16>, grid, dim3(256), ca);
 }
 
 // fp32 layers: vector-ALU kernels.  bf16 layers: matrix-core kernels.
 static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, int ksplit, const FfnArgs& f,
                                hipStream_t s) {
   if (dtype == SERE_F32) {
-    {
-      StageTimer tm(SERE_STAGE_GATE_UP, s);
-      hipLaunchKernelGGL(ffn_gateup_generic<SERE_F32>, dim3((inter + kGenJB - 1) / kGenJB, max_work), dim3(256), 0, s,
-                         f);
-    }
-    {
-      StageTimer tm(SERE_STAGE_DOWN, s);
-      hipLaunchKernelGGL(ffn_down_generic<SERE_F32>, dim3((hidden + kGenRB - 1) / kGenRB, max_work), dim3(256), 0, s,
-                         f);
-    }
+    launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_generic<SERE_F32>, dim3((inter + kGenJB - 1) / kGenJB, max_work),
+                 dim3(256), f);
+    launch_stage(SERE_STAGE_DOWN, s, ffn_down_generic<SERE_F32>, dim3((hidden + kGenRB - 1) / kGenRB, max_work),
+                 dim3(256), f);
   } else {
-    {
-      StageTimer tm(SERE_STAGE_GATE_UP, s);
-      hipLaunchKernelGGL(ffn_gateup_mfma, dim3(inter / (kGateUpJ * kWavesPerBlock), max_work), dim3(256), 0, s, f);
-    }
-    {
-      StageTimer tm(SERE_STAGE_DOWN, s);
-      hipLaunchKernelGGL(ffn_down_mfma,
-                         dim3(((hidden + kDownRows * kWavesPerBlock - 1) / (kDownRows * kWavesPerBlock)) * ksplit,
-                              max_work),
-                         dim3(256), 0, s, f);
-    }
+    launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_mfma, dim3(inter / (kGateUpJ * kWavesPerBlock), max_work),
+                 dim3(256), f);
+    launch_stage(SERE_STAGE_DOWN, s, ffn_down_mfma,
+                 dim3(((hidden + kDownRows * kWavesPerBlock - 1) / (kDownRows * kWavesPerBlock)) * ksplit, max_work),
+                 dim3(256), f);
   }
 }
 
