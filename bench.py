@@ -8,7 +8,7 @@ copies of the layer's weights so that the 256 MB last-level cache cannot serve
 them (a real model runs a different layer next).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
-                    [--S s] [--rho r] [--grid] [--sweep] [--no-graph]
+                    [--S s] [--rho r] [--grid] [--sweep] [--rho-sweep] [--no-graph]
 """
 from __future__ import annotations
 
@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="weight copies to rotate over (0: auto)")
     ap.add_argument("--grid", action="store_true", help="also time every (S, rho) of the workload")
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep")
+    ap.add_argument("--rho-sweep", action="store_true",
+                    help="also time thresholds 0.0 .. 1.0 at select_top_k = 1 (active experts and us)")
     ap.add_argument("--no-graph", action="store_true", help="plain stream launches, no HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-sere", action="store_true",
@@ -93,20 +95,22 @@ class Runner:
         for l in self.layers:
             l.set_knobs(S, rho)
 
-    def time(self, mode, steps, warmup):
-        """-> (mean us/step over exactly `steps` steps, per-round us list)."""
+    def time(self, mode, steps, warmup, hot=False):
+        """-> (mean us/step over exactly `steps` steps, per-round us list, host wall us/step).
+        hot: every step on the same copy of the weights (the last-level cache may serve them)."""
         torch = self.torch
-        n = len(self.layers)
+        layers = self.layers[:1] * len(self.layers) if hot else self.layers
+        n = len(layers)
         with torch.cuda.stream(self.stream):
             for i in range(warmup):
-                self._call(self.layers[i % n], mode)
+                self._call(layers[i % n], mode)
             self.stream.synchronize()
             graph = None
             if self.use_graph:
                 # one graph = one pass over all weight copies
                 graph = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(graph, stream=self.stream):
-                    for l in self.layers:
+                    for l in layers:
                         self._call(l, mode)
                 graph.replay()
                 self.stream.synchronize()
@@ -119,11 +123,11 @@ class Runner:
                 if graph is not None:
                     graph.replay()
                 else:
-                    for l in self.layers:
+                    for l in layers:
                         self._call(l, mode)
                 ev[r + 1].record(self.stream)
             for i in range(rem):
-                self._call(self.layers[i], mode)
+                self._call(layers[i], mode)
             ev[rounds + 1].record(self.stream)
             torch.cuda.synchronize()
             wall = time.perf_counter() - t0
@@ -209,7 +213,10 @@ def main():
         us, per_round, wall_us = run.time(mode, steps, warmup)
         n_exp = (nb if mode == "baseline" else na) + spec.shared
         gbs = n_exp * expert_bytes / us * 1e-3
+        pr = sorted(per_round)
+        pct = lambda q: round(pr[min(len(pr) - 1, int(q * len(pr)))], 2) if pr else None
         return {"us_per_step": round(us, 2), "median_round_us": round(statistics.median(per_round), 2) if per_round else None,
+                "p10_round_us": pct(0.10), "p90_round_us": pct(0.90),
                 "host_wall_us": round(wall_us, 2), "active_before": nb, "active_after": na,
                 "experts_read": n_exp, "expert_gb_per_s": round(gbs, 1),
                 "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
@@ -227,6 +234,7 @@ def main():
     base = measure("baseline", spec.top_k, 0.0, args.steps, args.warmup)
     run.set_knobs(args.S, args.rho)
     route_us, _, _ = run.time("route", min(args.steps, 200), 10)
+    hot_us, _, _ = run.time("sere", min(args.steps, 200), 10, hot=True)
 
     # roofline of the dominant kernel: the gate/up projection streams 2/3 of the
     # surviving experts' bytes
@@ -259,6 +267,7 @@ def main():
         "sere": sere, "no_reroute": base,
         "speedup_vs_no_reroute": round(base["us_per_step"] / sere["us_per_step"], 3),
         "route_only_us": round(route_us, 2),
+        "sere_hot_weights_us": round(hot_us, 2),
         "roofline": roofline,
         "paper_context": "paper: up to 2.0x whole-model decode speedup on NVIDIA H20 under vLLM; "
                          "MoE MLP 227 us/layer-step at batch 32 on H20 (not this machine, not the target)",
@@ -267,6 +276,10 @@ def main():
     if args.grid:
         result["grid"] = {f"S={S},rho={rho}": measure("sere", S, rho, args.steps, args.warmup)
                           for S, rho in spec.grid}
+    if args.rho_sweep:
+        result["rho_sweep"] = {f"{rho:.1f}": {k: v for k, v in measure("sere", 1, rho, 100, 10).items()
+                                              if k in ("us_per_step", "active_before", "active_after")}
+                               for rho in [i / 10 for i in range(11)]}
     if args.sweep:
         result["sweep"] = sweep(args)
     if not args.no_cpu_baseline:
