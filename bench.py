@@ -8,7 +8,7 @@ copies of the layer's weights so that the 256 MB last-level cache cannot serve
 them (a real model runs a different layer next).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
-                    [--S s] [--rho r] [--grid] [--sweep] [--rho-sweep] [--no-graph]
+                    [--S s] [--rho r] [--grid] [--sweep] [--rho-sweep] [--layers L] [--no-graph]
 """
 from __future__ import annotations
 
@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep")
     ap.add_argument("--rho-sweep", action="store_true",
                     help="also time thresholds 0.0 .. 1.0 at select_top_k = 1 (active experts and us)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="also time a chained stack of this many layers (x <- x + MoE(x), one HIP graph)")
     ap.add_argument("--no-graph", action="store_true", help="plain stream launches, no HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-sere", action="store_true",
@@ -282,9 +284,59 @@ def main():
                                for rho in [i / 10 for i in range(11)]}
     if args.sweep:
         result["sweep"] = sweep(args)
+    if args.layers > 0:
+        result["stack"] = stack(args, run)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, sim_host, args.S, args.rho, args.cpu_seconds)
     print(json.dumps(result))
+
+
+def stack(args, run):
+    """L chained layers (layer l reads what layer l-1 wrote; residual added by the
+    combine step), one HIP graph per pass; layer l uses weight copy l mod copies,
+    so consecutive layers never share cached weights.  Per-layer active counts."""
+    import torch
+    from paper_2602_07616_amd import binding as B, device
+    wl, n = run.wl, len(run.layers)
+    layers = []
+    for l in range(args.layers):
+        layer = device.DeviceLayer.from_workload(wl, run.sim, args.S, args.rho, weights=run.layers[l % n].weights())
+        layer.cfg.flags = B.SERE_FLAG_RESIDUAL
+        if layers:
+            layer.hidden = layers[-1].out
+        layers.append(layer)
+    out = {}
+    stream = run.stream
+    for label, reroute in (("sere", True), ("no_reroute", False)):
+        def one_pass(with_outputs):
+            for layer in layers:
+                if reroute:
+                    layer.run_decode(stream, with_outputs)
+                else:
+                    layer.run_baseline(stream, with_outputs)
+        with torch.cuda.stream(stream):
+            one_pass(True)
+            stream.synchronize()
+            counts = [layer.route.num_active.cpu().tolist() for layer in layers]
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                one_pass(False)
+            for _ in range(3):
+                graph.replay()
+            reps = max(1, args.steps // args.layers)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for _ in range(reps):
+                graph.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        out[label] = {"us_per_pass": round(us, 2), "us_per_layer": round(us / args.layers, 2),
+                      "active_before": [c[0] for c in counts], "active_after": [c[1] for c in counts]}
+    out["layers"] = args.layers
+    out["speedup_vs_no_reroute"] = round(out["no_reroute"]["us_per_pass"] / out["sere"]["us_per_pass"], 3)
+    return out
 
 
 def sweep(args):

@@ -51,9 +51,16 @@ extern "C" {
 #define SERE_ERR_BAD_DTYPE (-4)           /* dtype is neither SERE_F32 nor SERE_BF16     */
 #define SERE_ERR_MISALIGNED (-5)          /* a pointer is not 16-byte aligned            */
 #define SERE_ERR_WORKSPACE_TOO_SMALL (-6) /* workspace_bytes < sere_workspace_bytes()    */
-#define SERE_ERR_BAD_FLAGS (-7)           /* flags != 0                                  */
+#define SERE_ERR_BAD_FLAGS (-7)           /* flags has a bit no SERE_FLAG_* names        */
 #define SERE_ERR_NONFINITE_THRESHOLD (-8) /* threshold is NaN or infinite                */
 #define SERE_ERR_HIP (-9)                 /* a HIP launch reported an error              */
+
+/* sere_config.flags */
+#define SERE_FLAG_RESIDUAL 1 /* sere_moe_decode[_baseline]: out = hidden + layer(hidden), the
+                                residual connection around the MoE block of a decoder layer, added
+                                in fp32 before the one rounding to the output type; lets a stack
+                                of layers be chained with no kernel in between.  `out` must not
+                                overlap `hidden`.  Ignored by the routing-only entry points.   */
 
 #define SERE_MAX_EXPERTS 256
 #define SERE_MAX_SHARED 16
@@ -81,7 +88,7 @@ typedef struct sere_config {
   float threshold;      /* rho, finite; rho <= 0 disables the critical-expert test
                            (every secondary expert is re-routed), as in the paper's
                            re-routing algorithm                                     */
-  int32_t flags;        /* reserved, must be 0                                       */
+  int32_t flags;        /* 0 or an OR of SERE_FLAG_*                                 */
 } sere_config;
 
 /*

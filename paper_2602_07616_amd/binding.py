@@ -13,6 +13,8 @@ from typing import Optional
 SERE_F32 = 0
 SERE_BF16 = 1
 
+SERE_FLAG_RESIDUAL = 1
+
 SERE_OK = 0
 SERE_ERR_NULL_PTR = -1
 SERE_ERR_BAD_SHAPE = -2

@@ -135,12 +135,13 @@ struct CombineArgs {
   const float* y;            // [ksplit, R, dh]
   const float* topk_w;       // [T, K]
   const int32_t* slot_pos;   // [T*K]
+  const void* residual;      // [T, dh] added to the sum (the layer's input), or NULL
   void* out;                 // [T, dh]
   int T, dh, K, n_sh, ksplit, rows;
 };
 
-// out[t, r] = sum_k W[t,k] * y[pos(t,k), r] + sum_s y[A + s*T + t, r]; slots in
-// ascending k, then shared experts; fp32, one rounding to the output dtype.
+// out[t, r] = sum_k W[t,k] * y[pos(t,k), r] + sum_s y[A + s*T + t, r] (+ residual[t, r]); slots
+// in ascending k, then shared experts, then the residual; fp32, one rounding to the output dtype.
 // grid (ceil(dh/256), T), 256 threads.
 template <int DT>
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs p) {
@@ -161,6 +162,12 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs p) {
     float v = 0.0f;
     for (int s = 0; s < p.ksplit; ++s) v += p.y[s * slice + static_cast<size_t>(pos) * p.dh + r];
     acc += v;
+  }
+  if (p.residual != nullptr) {
+    if (DT == SERE_F32)
+      acc += static_cast<const float*>(p.residual)[static_cast<size_t>(t) * p.dh + r];
+    else
+      acc += bf16_to_f32(static_cast<const uint16_t*>(p.residual)[static_cast<size_t>(t) * p.dh + r]);
   }
   store1<DT>(p.out, static_cast<size_t>(t) * p.dh + r, acc);
 }

@@ -76,7 +76,7 @@ static Layout make_layout(const sere_config& c) {
 static int check_config(const sere_config* c) {
   if (c == nullptr) return SERE_ERR_NULL_PTR;
   if (c->dtype != SERE_F32 && c->dtype != SERE_BF16) return SERE_ERR_BAD_DTYPE;
-  if (c->flags != 0) return SERE_ERR_BAD_FLAGS;
+  if ((c->flags & ~SERE_FLAG_RESIDUAL) != 0) return SERE_ERR_BAD_FLAGS;
   if (c->num_tokens < 1 || c->num_tokens > SERE_MAX_TOKENS) return SERE_ERR_BAD_SHAPE;
   if (c->hidden < 64 || c->hidden % 64 != 0 || c->hidden > (1 << 16)) return SERE_ERR_BAD_SHAPE;
   if (c->inter < 64 || c->inter % 64 != 0 || c->inter > (1 << 18)) return SERE_ERR_BAD_SHAPE;
@@ -264,8 +264,10 @@ static int launch_route(const sere_config& c, const Pointers& p, bool with_topk,
   return hip_status();
 }
 
-static void launch_combine(const sere_config& c, const Layout& l, const Pointers& p, void* out, hipStream_t s) {
-  CombineArgs ca{p.y, p.topk_w, p.route.slot_pos, out, c.num_tokens, c.hidden, c.top_k, c.num_shared, l.ksplit, l.rows};
+static void launch_combine(const sere_config& c, const Layout& l, const Pointers& p, const void* hidden, void* out,
+                           hipStream_t s) {
+  CombineArgs ca{p.y, p.topk_w, p.route.slot_pos, (c.flags & SERE_FLAG_RESIDUAL) ? hidden : nullptr, out,
+                 c.num_tokens, c.hidden, c.top_k, c.num_shared, l.ksplit, l.rows};
   const dim3 grid((c.hidden + 255) / 256, c.num_tokens);
   if (c.dtype == SERE_F32)
     launch_stage(SERE_STAGE_COMBINE, s, combine_kernel<SERE_F32>, grid, dim3(256), ca);
@@ -293,7 +295,7 @@ static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, i
 static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
                        hipStream_t s) {
   launch_gateup_down(c.dtype, c.inter, c.hidden, l.max_work, l.ksplit, f, s);
-  launch_combine(c, l, p, out, s);
+  launch_combine(c, l, p, f.hidden, out, s);
 }
 
 // wide experts: h keeps its bf16 rounding residual in a second plane (see decode())
@@ -570,7 +572,7 @@ const char* sere_status_string(int status) {
     case SERE_ERR_BAD_DTYPE: return "dtype is neither SERE_F32 nor SERE_BF16";
     case SERE_ERR_MISALIGNED: return "a pointer is not sufficiently aligned";
     case SERE_ERR_WORKSPACE_TOO_SMALL: return "workspace is smaller than sere_workspace_bytes()";
-    case SERE_ERR_BAD_FLAGS: return "flags must be 0";
+    case SERE_ERR_BAD_FLAGS: return "flags has an unknown bit";
     case SERE_ERR_NONFINITE_THRESHOLD: return "threshold is NaN or infinite";
     case SERE_ERR_HIP: return "a HIP call reported an error";
     default: return "unknown status";

@@ -121,3 +121,47 @@ class DeviceLayer:
         import torch
         torch.cuda.synchronize()
         return self.out.detach().to(torch.float64).cpu().numpy()
+
+
+class DecodeStack:
+    """L consecutive MoE layers of a decoder chained on the device:
+    x_{l+1} = x_l + MoE_l(x_l) (the residual connection is added by the library's
+    combine step, SERE_FLAG_RESIDUAL), each layer with its own weights and its own
+    similarity matrix (Sec. 3.1.1: one matrix per layer).  Attention and
+    normalisation, which sit between MoE blocks in a real decoder, are not part of
+    this path.  Layer l reads the tensor layer l-1 wrote: no copy, no kernel in between.
+    """
+
+    def __init__(self, workloads, sims, S: int, rho: float, device="cuda", share_weights=False):
+        """workloads: one per layer (same shape); sims: one [M, M] matrix per layer.
+        share_weights: every layer uses layer 0's resident tensors (timing only)."""
+        self.layers = []
+        weights = None
+        for wl, sim in zip(workloads, sims):
+            layer = DeviceLayer.from_workload(wl, sim, S, rho, device, weights=weights if share_weights else None)
+            if share_weights and weights is None:
+                weights = layer.weights()
+            layer.cfg.flags = B.SERE_FLAG_RESIDUAL
+            if self.layers:
+                layer.hidden = self.layers[-1].out
+            self.layers.append(layer)
+
+    def set_knobs(self, S: int, rho: float) -> None:
+        for l in self.layers:
+            l.set_knobs(S, rho)
+
+    def run(self, stream=None, reroute=True, with_outputs=True) -> None:
+        for l in self.layers:
+            if reroute:
+                l.run_decode(stream, with_outputs)
+            else:
+                l.run_baseline(stream, with_outputs)
+
+    def active_counts(self):
+        """[(before, after)] per layer of the last run with outputs."""
+        import torch
+        torch.cuda.synchronize()
+        return [tuple(l.route.num_active.cpu().tolist()) for l in self.layers]
+
+    def out_to_host_f64(self) -> np.ndarray:
+        return self.layers[-1].out_to_host_f64()

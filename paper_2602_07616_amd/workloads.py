@@ -326,6 +326,13 @@ def custom_spec(name: str, dtype: int, hidden: int, experts: int, top_k: int, in
                      seed, seed, **kw)
 
 
+def stack_specs(spec: LayerSpec, layers: int) -> Tuple[LayerSpec, ...]:
+    """Specs of `layers` consecutive MoE layers of one model: same shape and
+    input batch, independent weights (layer l draws from weight_seed + 7919*l)."""
+    return tuple(replace(spec, name=f"{spec.name}.L{l}", weight_seed=spec.weight_seed + 7919 * l)
+                 for l in range(layers))
+
+
 def planted_similarity(spec: LayerSpec, seed: int) -> np.ndarray:
     """A synthetic [M, M] fp32 similarity matrix with the structure the paper
     reports for trained models (groups of similar experts, a unit diagonal,
