@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="weight copies to rotate over (0: auto)")
     ap.add_argument("--grid", action="store_true", help="also time every (S, rho) of the workload")
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep")
+    ap.add_argument("--prefill", action="store_true",
+                    help="also time prefill-sized batches (512, 1024, 2048 tokens) of the Qwen3-shaped layer")
     ap.add_argument("--rho-sweep", action="store_true",
                     help="also time thresholds 0.0 .. 1.0 at select_top_k = 1 (active experts and us)")
     ap.add_argument("--layers", type=int, default=0,
@@ -284,6 +286,8 @@ def main():
                                for rho in [i / 10 for i in range(11)]}
     if args.sweep:
         result["sweep"] = sweep(args)
+    if args.prefill:
+        result["prefill_sized"] = sweep(args, (512, 1024, 2048))
     if args.layers > 0:
         result["stack"] = stack(args, run)
     if not args.no_cpu_baseline:
@@ -339,12 +343,12 @@ def stack(args, run):
     return out
 
 
-def sweep(args):
+def sweep(args, batches=None):
     """Batch-size sweep on the Qwen3-shaped layer: active experts and latency."""
     from paper_2602_07616_amd import workloads as wk
     out = {}
     sim = None
-    for T in wk.BATCH_SWEEP:
+    for T in (batches or wk.BATCH_SWEEP):
         wl = wk.make_workload("qwen3_b128", tokens=T)
         run = Runner(wl, sim, 4, not args.no_graph)
         sim = run.sim
@@ -352,7 +356,7 @@ def sweep(args):
         for label, mode, S in (("no_reroute", "baseline", 8), ("S=2", "sere", 2), ("S=1", "sere", 1)):
             run.set_knobs(S, 0.0)
             nb, na = run.active(mode)
-            us, _, _ = run.time(mode, 200, 20)
+            us, _, _ = run.time(mode, 200 if T <= 256 else 40, 20 if T <= 256 else 4)
             row[label] = {"us_per_step": round(us, 2), "active": nb if mode == "baseline" else na}
         out[str(T)] = row
         del run

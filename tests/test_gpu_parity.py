@@ -200,6 +200,24 @@ def test_batch_sweep_decode(dev, T):
         check_output(got if tokens is None else got[tokens], want, wl.spec.dtype, f"T={T} S={S}")
 
 
+def test_prefill_sized_batch(dev):
+    """T = 1024 tokens of the Qwen3-shaped layer (the prefill regime of the paper's
+    appendix on prefill: nearly every expert is primary, nothing to skip).  Integers
+    for the whole batch, outputs on sampled tokens."""
+    T = 1024
+    wl, layer, sim = device_layer(dev, "qwen3_b128", T)
+    for S, rho in ((2, 0.0), (8, 0.0)):
+        print(f"prefill-sized T={T} S={S}", flush=True)
+        layer.set_knobs(S, rho)
+        layer.run_decode()
+        ref = oracle_route(wl, sim, S, rho, ("sweep", T))
+        check_routing(layer.routing_to_host(), ref, layer.cfg)
+        assert ref.n_active_after >= 0.9 * wl.spec.experts
+        tokens = list(range(3, T, 97))
+        want = oracle_output(wl, ref.rerouted_ids, ref.topk_weights, ("sweep", T), tokens)
+        check_output(layer.out_to_host_f64()[tokens], want, wl.spec.dtype, f"T={T} S={S}")
+
+
 # ------------------------------------------------------------ edge cases ---
 def small_case(dev, dtype, T, dh, M, K, dm, n_sh, seed, S, rho, sim=None, mutate=None):
     spec = wk.custom_spec(f"edge{seed}", dtype, dh, M, K, dm, n_sh, T, seed, weight_std=0.02,
@@ -223,6 +241,9 @@ EDGE = [
     (wk.BF16, 70, 64, 256, 5, 64, 0, 2, 0.4),      # maximum expert count
     (wk.BF16, 130, 256, 6, 2, 128, 0, 1, 0.0),     # many tokens per expert (> one tile)
     (wk.BF16, 9, 1024, 12, 6, 2112, 0, 3, 0.2),    # inter not a power of two, wide
+    (wk.BF16, 11, 128, 48, 12, 64, 0, 5, 0.3),     # K above twice the lanes per token (long-list merge)
+    (wk.BF16, 6, 64, 256, 40, 64, 1, 7, 0.0),      # maximum expert count with a large K
+    (wk.F32, 4, 64, 40, 40, 64, 0, 39, 0.0),       # K == M == 40, S = K - 1
 ]
 
 
