@@ -190,6 +190,20 @@ class OracleLib:
                                            dh, M, dm, _p(act), _p(sim))
         return sim
 
+    def similarity_cosine(self, calib, w_gate_up, w_down, dtype: int) -> np.ndarray:
+        """-> S [M,M] float64, the cosine metric of the appendix on similarity metrics."""
+        calib = _check(calib, dtype)
+        w_gate_up, w_down = _check(w_gate_up, dtype), _check(w_down, dtype)
+        N, n, dh = calib.shape
+        M, dm2, _ = w_gate_up.shape
+        dm = dm2 // 2
+        assert w_gate_up.shape == (M, 2 * dm, dh) and w_down.shape == (M, dh, dm)
+        act = np.empty((M, n, dh), dtype=np.float64)
+        sim = np.empty((M, M), dtype=np.float64)
+        self.c.oracle_similarity_cosine(_p(calib), _p(w_gate_up), _p(w_down), dtype, N, n,
+                                        dh, M, dm, _p(act), _p(sim))
+        return sim
+
     def route(self, hidden, router_w, dtype: int, K: int, sim, S: int,
               rho: float) -> LayerResult:
         """Routing half of the layer (no expert is executed)."""

@@ -28,6 +28,8 @@
  *                                   appendix "Frobenius Similarity" and the
  *                                   appendix algorithm "Expert Similarity
  *                                   Estimation"
+ *   cosine similarity matrix        the same, with the appendix "Cosine
+ *                                   Similarity"
  *
  * Readings taken where the paper leaves a choice (all listed in the design
  * notes of this repository):
@@ -406,4 +408,64 @@ void oracle_similarity_frobenius(const void *calib, const void *w_gate_up,
     for (size_t i = 0; i < (size_t)M * M; ++i)
         sim[i] /= (double)N;
     free(dist);
+}
+
+/*
+ * Expert-similarity matrix with the cosine metric (appendix "Cosine
+ * Similarity"): for each calibration batch, Sim(p,q) = (1/n) sum over the n
+ * tokens of <A_p[i], A_q[i]> / (||A_p[i]|| ||A_q[i]||), A_j = E_j(X) as above;
+ * S[p][q] += Sim(p,q) per batch, finally S /= N (Sec. 3.1.1).  A token for
+ * which either output is the zero vector contributes 0 (the quotient is
+ * undefined there; reading of this build).  act is caller scratch of M*n*dh
+ * doubles.
+ */
+void oracle_similarity_cosine(const void *calib, const void *w_gate_up, const void *w_down,
+                              int dtype, int N, int n, int dh, int M, int dm, double *act,
+                              double *sim)
+{
+    size_t gu = (size_t)2 * dm * dh, dn = (size_t)dh * dm;
+    double *norm = (double *)malloc(sizeof(double) * (size_t)M * n);
+    for (size_t i = 0; i < (size_t)M * M; ++i)
+        sim[i] = 0.0;
+    for (int b = 0; b < N; ++b) {
+#pragma omp parallel
+        {
+            double *scratch = (double *)malloc(sizeof(double) * (size_t)dm);
+#pragma omp for schedule(dynamic, 1) collapse(2)
+            for (int j = 0; j < M; ++j)
+                for (int r = 0; r < n; ++r)
+                    expert_ffn(elem_ptr(calib, dtype, ((size_t)b * n + r) * dh),
+                               elem_ptr(w_gate_up, dtype, (size_t)j * gu),
+                               elem_ptr(w_down, dtype, (size_t)j * dn), dtype, dh, dm,
+                               scratch, act + ((size_t)j * n + r) * dh);
+            free(scratch);
+        }
+        for (int j = 0; j < M; ++j)
+            for (int r = 0; r < n; ++r) {
+                const double *a = act + ((size_t)j * n + r) * dh;
+                double ss = 0.0;
+                for (int c = 0; c < dh; ++c)
+                    ss += a[c] * a[c];
+                norm[(size_t)j * n + r] = sqrt(ss);
+            }
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int p = 0; p < M; ++p)
+            for (int q = 0; q < M; ++q) {
+                double total = 0.0;
+                for (int r = 0; r < n; ++r) {
+                    const double *a = act + ((size_t)p * n + r) * dh;
+                    const double *c = act + ((size_t)q * n + r) * dh;
+                    double dot = 0.0;
+                    for (int k = 0; k < dh; ++k)
+                        dot += a[k] * c[k];
+                    double den = norm[(size_t)p * n + r] * norm[(size_t)q * n + r];
+                    if (den > 0.0)
+                        total += dot / den;
+                }
+                sim[(size_t)p * M + q] += total / (double)n;
+            }
+    }
+    for (size_t i = 0; i < (size_t)M * M; ++i)
+        sim[i] = sim[i] / (double)N;
+    free(norm);
 }

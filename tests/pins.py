@@ -478,7 +478,46 @@ def pin_similarity(o):
     assert s.min() == 0.0
 
 
+def pin_similarity_cosine(o):
+    """Cosine metric: numpy formulation with library norms; closed-form cases."""
+    for dtype, seed in ((wk.F32, 111), (wk.BF16, 112)):
+        c = rng_case(seed, dtype, 1, 24, 6, 10)
+        c["w_gate_up"][5] = c["w_gate_up"][2]
+        c["w_down"][5] = c["w_down"][2]                       # exact twin of expert 2
+        if dtype == wk.F32:
+            c["w_gate_up"][4] = c["w_gate_up"][1]
+            c["w_down"][4] = np.float32(-2.0) * c["w_down"][1]   # expert 4 = -2 x expert 1: cosine -1
+            c["w_gate_up"][3] = c["w_gate_up"][0]
+            c["w_down"][3] = np.float32(0.5) * c["w_down"][0]    # expert 3 = expert 0 / 2: cosine +1
+        cal = wk.to_storage(wk.std_normal(seed, "cal", 3 * 5 * 24), dtype).reshape(3, 5, 24)
+        s = o.similarity_cosine(cal, c["w_gate_up"], c["w_down"], dtype)
+        N, M = cal.shape[0], c["w_gate_up"].shape[0]
+        want = np.zeros((M, M))
+        for b in range(N):
+            acts = [np_expert(f64(cal[b], dtype), f64(c["w_gate_up"][e], dtype), f64(c["w_down"][e], dtype))
+                    for e in range(M)]
+            unit = [a / np.linalg.norm(a, axis=1, keepdims=True) for a in acts]
+            want += np.array([[np.mean(np.sum(unit[p] * unit[q], axis=1)) for q in range(M)] for p in range(M)])
+        want /= N
+        assert np.allclose(s, want, rtol=1e-11, atol=1e-13)
+        assert np.allclose(s, s.T, rtol=0, atol=1e-15)
+        assert np.allclose(np.diag(s), 1.0, atol=1e-14)
+        assert s.min() >= -1.0 - 1e-14 and s.max() <= 1.0 + 1e-14
+        assert abs(s[2, 5] - 1.0) < 1e-14
+        if dtype == wk.F32:
+            assert abs(s[1, 4] + 1.0) < 1e-12 and abs(s[0, 3] - 1.0) < 1e-12   # scale-invariant, sign-aware
+            fro = o.similarity_frobenius(cal, c["w_gate_up"], c["w_down"], dtype)
+            assert fro[0, 3] < 1.0 - 1e-3           # the Frobenius metric is NOT scale-invariant: a different quantity
+    # a zero output vector contributes 0: expert 1 with zero down weights
+    c = rng_case(113, wk.F32, 1, 16, 3, 4)
+    c["w_down"][1] = 0
+    cal = wk.std_normal(113, "cal", 2 * 4 * 16).reshape(2, 4, 16)
+    s = o.similarity_cosine(cal, c["w_gate_up"], c["w_down"], wk.F32)
+    assert np.all(s[1] == 0.0) and np.all(s[:, 1] == 0.0) and abs(s[0, 0] - 1.0) < 1e-14
+
+
 ALL_PINS = [
+    pin_similarity_cosine,
     pin_router_logits_library, pin_topk_order_and_gate, pin_fig2_behaviour,
     pin_reroute_hand_cases, pin_reroute_against_brute, pin_reroute_invariants, pin_compact,
     pin_expert_closed_form, pin_layer_dense_formulation, pin_shared_experts_closed_form,

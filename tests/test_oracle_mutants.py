@@ -52,6 +52,12 @@ MUTANTS = [
      [pins.pin_similarity]),
     ("frobenius_not_inverted", "1.0 - dist[i] / max_dist", "dist[i] / max_dist", [pins.pin_similarity]),
     ("similarity_not_averaged", "sim[i] /= (double)N;", "sim[i] /= 1.0;", [pins.pin_similarity]),
+    ("cosine_not_normalised", "total += dot / den;", "total += dot;", [pins.pin_similarity_cosine]),
+    ("cosine_not_token_mean", "sim[(size_t)p * M + q] += total / (double)n;", "sim[(size_t)p * M + q] += total;",
+     [pins.pin_similarity_cosine]),
+    ("cosine_norm_no_sqrt", "norm[(size_t)j * n + r] = sqrt(ss);", "norm[(size_t)j * n + r] = ss;",
+     [pins.pin_similarity_cosine]),
+    ("cosine_not_averaged", "sim[i] = sim[i] / (double)N;", "sim[i] = sim[i];", [pins.pin_similarity_cosine]),
 ]
 
 
