@@ -61,6 +61,9 @@ extern "C" {
                                 in fp32 before the one rounding to the output type; lets a stack
                                 of layers be chained with no kernel in between.  `out` must not
                                 overlap `hidden`.  Ignored by the routing-only entry points.   */
+#define SERE_FLAG_SIM_COSINE 2 /* sere_similarity: the cosine metric instead of the Frobenius one
+                                 (appendix on similarity metrics); ignored by the other entry
+                                 points                                                        */
 
 #define SERE_MAX_EXPERTS 256
 #define SERE_MAX_SHARED 16
@@ -190,6 +193,11 @@ int sere_moe_decode_baseline(const sere_config *cfg, const void *hidden, const v
  * `num_batches` batches of `batch_tokens` tokens every routed expert is run on
  * every token, x_pq = ||A_p - A_q||_F, Sim(p,q) = 1 - x_pq / max over all pairs
  * of that batch, and sim = the mean of Sim over the batches (diagonal 1).
+ * With SERE_FLAG_SIM_COSINE in cfg->flags the metric is the cosine one of the
+ * appendix "Cosine Similarity" instead: Sim(p,q) = the mean over the batch's
+ * tokens of the cosine between the two experts' outputs for that token (a
+ * token where either output is the zero vector contributes 0); values lie in
+ * [-1, 1].
  *   calib [num_batches, batch_tokens, d_h]  dtype, device
  *   sim   [M, M] fp32, device, written
  * Uses cfg->hidden, num_experts, inter, dtype (the other fields must be valid

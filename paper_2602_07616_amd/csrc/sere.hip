@@ -76,7 +76,7 @@ static Layout make_layout(const sere_config& c) {
 static int check_config(const sere_config* c) {
   if (c == nullptr) return SERE_ERR_NULL_PTR;
   if (c->dtype != SERE_F32 && c->dtype != SERE_BF16) return SERE_ERR_BAD_DTYPE;
-  if ((c->flags & ~SERE_FLAG_RESIDUAL) != 0) return SERE_ERR_BAD_FLAGS;
+  if ((c->flags & ~(SERE_FLAG_RESIDUAL | SERE_FLAG_SIM_COSINE)) != 0) return SERE_ERR_BAD_FLAGS;
   if (c->num_tokens < 1 || c->num_tokens > SERE_MAX_TOKENS) return SERE_ERR_BAD_SHAPE;
   if (c->hidden < 64 || c->hidden % 64 != 0 || c->hidden > (1 << 16)) return SERE_ERR_BAD_SHAPE;
   if (c->inter < 64 || c->inter % 64 != 0 || c->inter > (1 << 18)) return SERE_ERR_BAD_SHAPE;
@@ -523,13 +523,18 @@ int sere_similarity(const sere_config* cfg, const void* calib, int32_t num_batch
                      const_cast<int32_t*>(f.work_off), const_cast<int32_t*>(f.work_cnt),
                      const_cast<int32_t*>(f.n_work));
   const size_t eb = cfg->dtype == SERE_F32 ? 4 : 2;
+  const int cosine = (cfg->flags & SERE_FLAG_SIM_COSINE) ? 1 : 0;
   for (int b = 0; b < num_batches; ++b) {
     f.hidden = static_cast<const char*>(calib) + static_cast<size_t>(b) * n * cfg->hidden * eb;
     launch_gateup_down(cfg->dtype, cfg->inter, cfg->hidden, M, l.ksplit, f, s);
-    hipLaunchKernelGGL(pair_distance_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, M,
-                       reinterpret_cast<double*>(ws + l.dist));
+    if (cosine)
+      hipLaunchKernelGGL(pair_cosine_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, M,
+                         reinterpret_cast<double*>(ws + l.dist));
+    else
+      hipLaunchKernelGGL(pair_distance_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden,
+                         M, reinterpret_cast<double*>(ws + l.dist));
     hipLaunchKernelGGL(similarity_accumulate_kernel, dim3(1), dim3(1024), 0, s,
-                       reinterpret_cast<const double*>(ws + l.dist), M, b, num_batches,
+                       reinterpret_cast<const double*>(ws + l.dist), M, b, num_batches, cosine,
                        reinterpret_cast<double*>(ws + l.acc), sim);
   }
   return hip_status();

@@ -34,15 +34,16 @@ def to_host(t, dtype: int) -> np.ndarray:
     return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def similarity_on_device(wl: Workload, weights=None, device="cuda"):
+def similarity_on_device(wl: Workload, weights=None, device="cuda", metric="frobenius"):
     """Expert-similarity matrix of the workload's layer from its calibration
     tokens, computed by the library (sere_similarity); returns a device fp32 [M, M]
-    tensor.  `weights` = (router_w, w_gate_up, w_down, ...) already on the device."""
+    tensor.  `weights` = (router_w, w_gate_up, w_down, ...) already on the device.
+    metric: "frobenius" | "cosine"."""
     import torch
     sp = wl.spec
     n_batches, n_tokens = wl.calib.shape[0], wl.calib.shape[1]
     cfg = B.make_config(n_tokens, sp.hidden, sp.experts, min(sp.top_k, sp.experts), sp.inter, 0,
-                        sp.dtype, 1, 0.0)
+                        sp.dtype, 1, 0.0, {"frobenius": 0, "cosine": B.SERE_FLAG_SIM_COSINE}[metric])
     gu = to_device(wl.w_gate_up, sp.dtype, device) if weights is None else weights[1]
     dn = to_device(wl.w_down, sp.dtype, device) if weights is None else weights[2]
     calib = to_device(wl.calib, sp.dtype, device)

@@ -53,7 +53,7 @@ BAD_CONFIGS = [
     ("num_shared", 17, B.SERE_ERR_BAD_SHAPE), ("top_k", 0, B.SERE_ERR_BAD_TOPK),
     ("top_k", 129, B.SERE_ERR_BAD_TOPK), ("select_top_k", 0, B.SERE_ERR_BAD_TOPK),
     ("select_top_k", 9, B.SERE_ERR_BAD_TOPK), ("dtype", 2, B.SERE_ERR_BAD_DTYPE),
-    ("flags", 2, B.SERE_ERR_BAD_FLAGS), ("flags", -1, B.SERE_ERR_BAD_FLAGS), ("threshold", float("nan"), B.SERE_ERR_NONFINITE_THRESHOLD),
+    ("flags", 4, B.SERE_ERR_BAD_FLAGS), ("flags", -1, B.SERE_ERR_BAD_FLAGS), ("threshold", float("nan"), B.SERE_ERR_NONFINITE_THRESHOLD),
     ("threshold", float("inf"), B.SERE_ERR_NONFINITE_THRESHOLD),
 ]
 FAKE = 0x10000  # aligned, non-NULL, never dereferenced: validation fails first

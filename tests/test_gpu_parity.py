@@ -374,6 +374,24 @@ def test_similarity_parity(dev, name):
         assert int(np.argmax(row)) == b
 
 
+@pytest.mark.parametrize("name", ["tiny", "qwen15_b32"])
+def test_similarity_cosine_parity(dev, name):
+    """The cosine metric of sere_similarity against the oracle's.  Cosines of
+    independent random experts are near 0 and those of twins near 1; bf16 layers
+    carry the bf16 rounding of h in both outputs (same tolerance as above)."""
+    wl, layer, _ = device_layer(dev, name)
+    print(f"cosine similarity {name}", flush=True)
+    got = dev.similarity_on_device(wl, layer.weights(), metric="cosine").cpu().numpy()
+    want = oracle.similarity_cosine(wl.calib, wl.w_gate_up, wl.w_down, wl.spec.dtype)
+    tol = 1e-5 if wl.spec.dtype == wk.F32 else 5e-3
+    assert np.abs(got - want).max() <= tol, np.abs(got - want).max()
+    assert np.allclose(np.diag(got), 1.0, atol=1e-6)
+    sp = wl.spec
+    if sp.twin_n:
+        twins = [got[sp.twin_src + i, sp.twin_dst + i] for i in range(sp.twin_n)]
+        assert min(twins) > 0.9 and np.abs(got - np.eye(sp.experts)).max() > 0.9
+
+
 def test_similarity_feeds_routing(dev):
     """The library's own similarity matrix drives the same re-routing as the
     oracle's on the tiny fp32 layer (values agree to 1e-5 and no two candidate
