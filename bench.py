@@ -32,6 +32,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 # (workload, select_top_k, threshold); other configurations report null.
 MEASURED_TRAFFIC = {
     ("qwen3_b32", 2, 0.0): {"gate_up": 204660005, "down": 106605993},
+    ("qwen3_b128", 2, 0.0): {"gate_up": 661108337, "down": 350124011},
+    ("mixtral_b64", 2, 0.0): {"gate_up": 1890645979, "down": 1061036283},
 }
 
 
