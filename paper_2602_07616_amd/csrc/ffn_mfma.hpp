@@ -102,7 +102,9 @@ struct Stage {
   static constexpr int kPerThread = kRows * kPiecesPerRow / 256;
   static_assert(kPerThread >= 1 && kRows * kPiecesPerRow % 256 == 0, "chunk must split over 256 threads");
 };
-constexpr int kStageLdsBytes = 2 * Stage<2, 256>::kBufBytes;  // the largest configuration, two buffers
+// the largest configurations, two buffers each
+constexpr int kStageLdsBytes = 2 * (Stage<4, 128>::kBufBytes > Stage<2, 256>::kBufBytes ? Stage<4, 128>::kBufBytes
+                                                                                        : Stage<2, 256>::kBufBytes);
 
 // Token rows of a group: row r (< nrows) of the group is row index[first + r]
 // (or first + r if index is NULL) of a matrix with leading dimension ld.
@@ -136,22 +138,22 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
   const int len = kend - kbeg;
   const int nch = (len + KC - 1) / KC;
 
-  // This thread's pieces of a chunk: (row, 16-byte column) pairs, the same for every chunk.
+  // This thread's pieces of a chunk, the same for every chunk: ONE token row (256 / rows
+  // threads share a row) and every kThreadsPerRow-th 16-byte piece of it, so that one row
+  // address and compile-time strides describe them all.
   // Every load below is unconditional (rows beyond nrows re-read row 0, columns beyond kend
   // re-read the last valid ones; what they deliver is finite and never used): with loads
   // under branches the compiler can no longer count outstanding loads and waits for ALL of
   // them before every use, which would serialise the prefetch.
-  const uint16_t* src[St::kPerThread];
-  int dst[St::kPerThread], col[St::kPerThread];
-#pragma unroll
-  for (int j = 0; j < St::kPerThread; ++j) {
-    const int pc = tid + 256 * j;
-    const int row = pc / St::kPiecesPerRow;
-    col[j] = (pc % St::kPiecesPerRow) * 8;
-    dst[j] = row * St::kRowBytes + col[j] * 2;
-    const int r = row < tok.nrows ? row : 0;
-    src[j] = tok.base + static_cast<size_t>(tok.index != nullptr ? tok.index[tok.first + r] : tok.first + r) * tok.ld;
-  }
+  constexpr int kThreadsPerRow = 256 / St::kRows;
+  static_assert(St::kPiecesPerRow % kThreadsPerRow == 0 && St::kPiecesPerRow / kThreadsPerRow == St::kPerThread,
+                "a row's pieces must split evenly over its threads");
+  const int srow = tid / kThreadsPerRow;
+  const int col0 = (tid % kThreadsPerRow) * 8;  // elements; piece j sits kThreadsPerRow * 8 * j further
+  const int dst0 = srow * St::kRowBytes + col0 * 2;
+  const int srow_ok = srow < tok.nrows ? srow : 0;
+  const uint16_t* src =
+      tok.base + static_cast<size_t>(tok.index != nullptr ? tok.index[tok.first + srow_ok] : tok.first + srow_ok) * tok.ld;
   auto chunk_start = [&](int c) {
     int cc = c + rot;
     if (cc >= nch) cc -= nch;
@@ -163,14 +165,14 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
     for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
       for (int j = 0; j < St::kPerThread; ++j)
-        stage[pl][j] = load_reused(src[j] + pl * lo_plane + min(k0 + col[j], kend - 8));
+        stage[pl][j] = load_reused(src + pl * lo_plane + min(k0 + col0 + kThreadsPerRow * 8 * j, kend - 8));
   };
   auto store_tokens = [&](int buf) {
 #pragma unroll
     for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
       for (int j = 0; j < St::kPerThread; ++j)
-        *reinterpret_cast<u32x4*>(lds + (buf * NP + pl) * St::kBufBytes + dst[j]) = stage[pl][j];
+        *reinterpret_cast<u32x4*>(lds + (buf * NP + pl) * St::kBufBytes + dst0 + kThreadsPerRow * 16 * j) = stage[pl][j];
   };
   // weights of one half of a chunk: k blocks [b0, b1)
   u32x4 xa[NA][H0], ya[NA][H0], xb[NA][H0], yb[NA][H0];
@@ -344,7 +346,10 @@ __global__ __launch_bounds__(256, 4) void ffn_gateup_mfma(FfnArgs p) {
     if (cnt <= kTile) {
       gateup_group<1, 256, false>(p, W, j0, off, cnt, lds);
     } else {
-      for (int q = 0; q < cnt; q += 2 * kTile) gateup_group<2, 256, false>(p, W, j0, off + q, min(2 * kTile, cnt - q), lds);
+      // long items (many tokens per expert): 64 rows per pass over the weights while more than 32 remain
+      int q = 0;
+      for (; cnt - q > 2 * kTile; q += 4 * kTile) gateup_group<4, 128, false>(p, W, j0, off + q, min(4 * kTile, cnt - q), lds);
+      if (q < cnt) gateup_group<2, 256, false>(p, W, j0, off + q, cnt - q, lds);
     }
   }
 }
@@ -437,12 +442,14 @@ __global__ __launch_bounds__(256, 4) void ffn_down_mfma(FfnArgs p) {
         down_group<2, 1, 128, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
       }
     } else {
-      for (int q = 0; q < cnt; q += 2 * kTile) {
-        if (p.split_h) {
+      if (p.split_h) {
+        for (int q = 0; q < cnt; q += 2 * kTile)
           down_group<2, 2, 64, true>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
-        } else {
-          down_group<2, 2, 128, false>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
-        }
+      } else {
+        int q = 0;
+        for (; cnt - q > 2 * kTile; q += 4 * kTile)
+          down_group<2, 4, 64, false>(p, W, r0, kbeg, kend, slice, off + q, min(4 * kTile, cnt - q), lds);
+        if (q < cnt) down_group<2, 2, 128, false>(p, W, r0, kbeg, kend, slice, off + q, cnt - q, lds);
       }
     }
   }

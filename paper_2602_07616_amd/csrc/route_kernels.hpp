@@ -292,11 +292,12 @@ struct RouteArgs {
   int32_t* work_cnt;        // [max items] rows of the item (1 .. kItemRows)
   int32_t* n_work;          // [2]: number of items; 1 if the FFN kernels are to cut them fine
   int fine_items;           // ... which they do while there are at most this many items
+  int item_rows;            // rows per work item: kItemRows, or twice that for batches with many rows per expert
 };
 
 constexpr int kRouteThreads = 1024;
 constexpr int kRouteWaves = kRouteThreads / kWave;
-constexpr int kItemRows = 32;                     // rows of the sorted slot list per FFN work item
+constexpr int kItemRows = 32;                     // rows of the sorted slot list per FFN work item (RouteArgs::item_rows may double it)
 constexpr int kIdsInLds = 4096;                   // slots whose ids a lone workgroup keeps in LDS
 
 struct RouteShared {
@@ -432,7 +433,8 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
   const bool is_e = tid < SERE_MAX_EXPERTS;
   const int my_cnt = (is_e && tid < M) ? s.cnt_a[tid] : 0;
   const int my_act = my_cnt > 0 ? 1 : 0;
-  const int my_items = (my_cnt + kItemRows - 1) / kItemRows;
+  const int item_rows = p.item_rows;
+  const int my_items = (my_cnt + item_rows - 1) / item_rows;
   int inc_cnt = my_cnt, inc_act = my_act, inc_items = my_items;
   if (is_e) {  // wave-uniform (waves 0-3)
 #pragma unroll
@@ -475,23 +477,23 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
     const int first = inc_items - my_items;
     for (int j = 0; j < my_items; ++j) {
       p.work_expert[first + j] = tid;
-      p.work_off[first + j] = off + j * kItemRows;
-      p.work_cnt[first + j] = min(kItemRows, my_cnt - j * kItemRows);
+      p.work_off[first + j] = off + j * item_rows;
+      p.work_cnt[first + j] = min(item_rows, my_cnt - j * item_rows);
     }
   }
-  const int sh_items = (p.T + kItemRows - 1) / kItemRows;  // per shared expert
+  const int sh_items = (p.T + item_rows - 1) / item_rows;  // per shared expert
   if (tid == 0) {
     p.expert_offsets[M] = A;
     p.num_active[0] = n_before;
     p.num_active[1] = n_after;
     p.n_work[0] = n_items + p.n_sh * sh_items;
-    p.n_work[1] = n_items + p.n_sh * sh_items <= p.fine_items ? 1 : 0;
+    p.n_work[1] = (item_rows == kItemRows && n_items + p.n_sh * sh_items <= p.fine_items) ? 1 : 0;
   }
   for (int i = tid; i < p.n_sh * sh_items; i += kRouteThreads) {
     const int sh = i / sh_items, j = i % sh_items;
     p.work_expert[n_items + i] = M + sh;
-    p.work_off[n_items + i] = A + sh * p.T + j * kItemRows;
-    p.work_cnt[n_items + i] = min(kItemRows, p.T - j * kItemRows);
+    p.work_off[n_items + i] = A + sh * p.T + j * item_rows;
+    p.work_cnt[n_items + i] = min(item_rows, p.T - j * item_rows);
   }
   for (int i = tid; i < p.n_sh * p.T; i += kRouteThreads) p.sorted_token[A + i] = i % p.T;
   lds_barrier();

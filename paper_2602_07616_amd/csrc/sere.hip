@@ -216,6 +216,8 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
   r.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
   r.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
   r.fine_items = kFineCutBlocks / (c.inter / (2 * kGateUpJ * kWavesPerBlock));
+  // many rows per expert on average (prefill-sized batches): items of 64 rows, served 64 at a time
+  r.item_rows = static_cast<long long>(c.num_tokens) * c.top_k >= 24ll * c.num_experts ? 2 * kItemRows : kItemRows;
   p.h = reinterpret_cast<float*>(ws + l.h);
   p.y = reinterpret_cast<float*>(ws + l.y);
   return p;
