@@ -166,6 +166,73 @@ __global__ __launch_bounds__(256) void router_logits_kernel(
   }
 }
 
+// The same for batches of many tokens: a workgroup serves TB tokens with its 16 experts, so a
+// router row is fetched once per TB tokens (at 2048 tokens the one-token kernel reads the
+// router weights 2048 times from cache).  Wave w: experts bx*16 + 4w .. +3 x tokens
+// by*TB .. +TB-1, one 512-wide chunk of the rows at a time.  Same lane pattern per logit as
+// above.  grid (ceil(M/16), ceil(T/TB)), 256 threads.
+template <int DT, int TB>
+__global__ __launch_bounds__(256) void router_logits_tokens_kernel(
+    const void* __restrict__ hidden, const void* __restrict__ router_w, uint64_t* __restrict__ list_key,
+    uint8_t* __restrict__ list_id, int T, int M, int dh, int32_t* clear_word) {
+  __shared__ double s_logit[TB][16];
+  const int t0 = blockIdx.y * TB;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (clear_word != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *clear_word = 0;
+  const int e0 = blockIdx.x * 16 + wave * 4;
+  double acc[4][TB];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int b = 0; b < TB; ++b) acc[q][b] = 0.0;
+  for (int i = lane * 8; i < dh; i += 512) {
+    Raw8<DT> xr[TB], wr[4];
+#pragma unroll
+    for (int b = 0; b < TB; ++b) xr[b].load(hidden, static_cast<size_t>(min(t0 + b, T - 1)) * dh + i);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) wr[q].load(router_w, static_cast<size_t>(min(e0 + q, M - 1)) * dh + i);
+    double wd[4][8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float wv[8];
+      wr[q].widen(wv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) wd[q][j] = static_cast<double>(wv[j]);
+    }
+#pragma unroll
+    for (int b = 0; b < TB; ++b) {
+      float xv[8];
+      xr[b].widen(xv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const double xd = static_cast<double>(xv[j]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q][b] = fma(xd, wd[q][j], acc[q][b]);
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int b = 0; b < TB; ++b) {
+      const double sum = wave_sum_dpp(acc[q][b]);
+      if (lane == 0) s_logit[b][wave * 4 + q] = sum;
+    }
+  __syncthreads();
+  if (threadIdx.x < 16 * TB) {  // one 16-lane row per token
+    const int b = threadIdx.x >> 4, t = t0 + b;
+    const int e = blockIdx.x * 16 + (threadIdx.x & 15);
+    const uint64_t key = e < M ? sortable_key(s_logit[b][threadIdx.x & 15]) : 0ull;
+    uint32_t rank = 0;
+    rank_step<1>(key, static_cast<uint32_t>(e), rank);
+    if (t < T) {
+      const size_t at = (static_cast<size_t>(t) * gridDim.x + blockIdx.x) * 16 + rank;
+      list_key[at] = key;
+      list_id[at] = static_cast<uint8_t>(e);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Ordered top-K and gate by merging the sorted lists.  LP (4, 8 or 16) adjacent
 // lanes own one token, lane l of the group holds list l (all 16 entries, in

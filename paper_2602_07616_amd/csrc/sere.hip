@@ -216,8 +216,10 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
   r.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
   r.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
   r.fine_items = kFineCutBlocks / (c.inter / (2 * kGateUpJ * kWavesPerBlock));
-  // many rows per expert on average (prefill-sized batches): items of 64 rows, served 64 at a time
-  r.item_rows = static_cast<long long>(c.num_tokens) * c.top_k >= 24ll * c.num_experts ? 2 * kItemRows : kItemRows;
+  // many rows per expert on average (prefill-sized batches): items of 64 or 128 rows, served in one
+  // pass over the weights each
+  const long long slots = static_cast<long long>(c.num_tokens) * c.top_k;
+  r.item_rows = slots >= 48ll * c.num_experts ? 4 * kItemRows : (slots >= 24ll * c.num_experts ? 2 * kItemRows : kItemRows);
   p.h = reinterpret_cast<float*>(ws + l.h);
   p.y = reinterpret_cast<float*>(ws + l.y);
   return p;
@@ -225,9 +227,23 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
 
 static int hip_status() { return hipGetLastError() == hipSuccess ? SERE_OK : SERE_ERR_HIP; }
 
+constexpr int kRouterTokensPerBlock = 4;  // batches of >= 256 tokens: a router row serves 4 tokens per fetch
+
 static int launch_router(const sere_config& c, const Pointers& p, const void* hidden,
                          const void* router_w, hipStream_t s) {
-  const dim3 grid((c.num_experts + 15) / 16, c.num_tokens);
+  const int lists = (c.num_experts + 15) / 16;
+  if (c.num_tokens >= 256) {
+    const dim3 grid(lists, (c.num_tokens + kRouterTokensPerBlock - 1) / kRouterTokensPerBlock);
+    if (c.dtype == SERE_F32)
+      launch_stage(SERE_STAGE_ROUTER, s, router_logits_tokens_kernel<SERE_F32, kRouterTokensPerBlock>, grid, dim3(256),
+                   hidden, router_w, p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
+    else
+      launch_stage(SERE_STAGE_ROUTER, s, router_logits_tokens_kernel<SERE_BF16, kRouterTokensPerBlock>, grid,
+                   dim3(256), hidden, router_w, p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden,
+                   p.ticket);
+    return hip_status();
+  }
+  const dim3 grid(lists, c.num_tokens);
   if (c.dtype == SERE_F32)
     launch_stage(SERE_STAGE_ROUTER, s, router_logits_kernel<SERE_F32>, grid, dim3(256), hidden, router_w, p.list_key,
                  p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
