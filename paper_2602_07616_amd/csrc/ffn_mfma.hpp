@@ -22,8 +22,9 @@
 // chunk 2g for A_even, chunk 2g+1 for A_odd.  Both MFMAs accumulate into the
 // same 16x16 tile (the order of k inside a dot product is free as long as both
 // operands agree).  The accumulator of lane (g, n) holds D[4*g + r][n],
-// r = 0..3.  No LDS, no barrier: a wavefront owns its tile from first load to
-// store.
+// r = 0..3.  The weights go from HBM to registers to the matrix cores and
+// nowhere else; the token operand, which the four wavefronts of a workgroup
+// share, is staged through LDS (below).
 //
 // Expert equations: appendix "Preliminaries on MoEs",
 // E(x) = (silu(x W_gate) * (x W_up)) W_down.

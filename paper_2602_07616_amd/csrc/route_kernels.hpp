@@ -10,9 +10,10 @@
 // rewritten map is counted, prefix-summed and regrouped per expert by the
 // same workgroup, in LDS.
 //
-// Two launches: (1) router logits, (2) top-K per token with one wavefront per
-// token; the workgroup that finishes last (a ticket in global memory, cleared
-// by launch 1) then runs the batch-wide step, so no third launch is needed.
+// Two launches: (1) router logits, delivered per token as sorted lists of 16;
+// (2) top-K per token as a merge of the list heads; the workgroup that finishes
+// last (a ticket in global memory, cleared by launch 1) then runs the
+// batch-wide step, so no third launch is needed.
 #pragma once
 
 #include "common.hpp"
