@@ -64,6 +64,10 @@ def load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         from . import build as _build
         _build.build(force=True)
+    # PyTorch ships its own copy of the HIP runtime; it must be in the process before this
+    # library is, so that both bind to the same one (two runtimes in one process do not
+    # share devices, streams or memory)
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     cfgp, outp = ctypes.POINTER(sere_config), ctypes.POINTER(sere_route_out)
