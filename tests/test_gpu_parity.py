@@ -268,6 +268,43 @@ def test_edge_cases(dev, case):
     assert (layer.out == a).all()
 
 
+def _random_configs(n=18, seed=20260):
+    """Seeded random small layers: ragged token counts, odd expert counts, few experts with many
+    tokens (work items of 64 and 128 rows), shared experts, both dtypes, thresholds on and off."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        dtype = wk.F32 if i % 6 == 5 else wk.BF16
+        M = int(rng.choice([2, 3, 5, 8, 17, 33, 70]))
+        K = int(rng.integers(1, min(M, 6) + 1))
+        T = int(rng.choice([1, 2, 7, 16, 17, 33, 65, 100, 190, 300]))
+        if T > 100 and M > 8:
+            T = int(rng.choice([33, 65, 100]))
+        dh = int(rng.choice([64, 128, 320, 512]))
+        dm = int(rng.choice([64, 128, 192, 448]))
+        n_sh = int(rng.choice([0, 0, 1, 2]))
+        S = int(rng.integers(1, K + 1))
+        rho = float(rng.choice([0.0, 0.0, 0.3, 0.6]))
+        out.append((dtype, T, dh, M, K, dm, n_sh, S, rho))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_configs(), ids=lambda c: "x".join(str(v) for v in c))
+def test_random_small_configs(dev, case):
+    dtype, T, dh, M, K, dm, n_sh, S, rho = case
+    print(f"random {case}", flush=True)
+    wl, layer, sim = small_case(dev, dtype, T, dh, M, K, dm, n_sh, 8100 + 7 * T + M + K, S, rho)
+    ref = oracle.layer(wl.hidden, wl.router_w, wl.w_gate_up, wl.w_down, wl.shared_gate_up,
+                       wl.shared_down, dtype, K, sim, S, rho)
+    if ref.min_gap <= 1e-9:
+        pytest.skip("near-tie in the router ordering for this seed")
+    layer.run_decode()
+    check_routing(layer.routing_to_host(), ref, layer.cfg)
+    check_output(layer.out_to_host_f64(), ref.out_sere, dtype, "sere")
+    layer.run_baseline()
+    check_output(layer.out_to_host_f64(), ref.out_base, dtype, "baseline")
+
+
 def test_identical_tokens_and_duplicate_router_rows(dev):
     """Exact ties: all tokens equal, and router rows 3 and 5 bit-identical, so
     their logits tie exactly and the lower index must rank first."""
