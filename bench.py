@@ -24,6 +24,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
+GRAPH_STEPS = 32          # decode steps captured in one HIP graph (see Runner.time)
 
 # HBM bytes per launch (read + write) of the two FFN kernels, from rocprofv3 --pmc FETCH_SIZE
 # and --pmc WRITE_SIZE runs of `bench.py --only-sere --copy-calibration --no-graph`, each counter
@@ -40,7 +41,7 @@ MEASURED_TRAFFIC = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--steps", type=int, default=384)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--workload", default="qwen3_b32")
     ap.add_argument("--S", type=int, default=2, help="select_top_k of the headline SERE step")
@@ -102,25 +103,29 @@ class Runner:
             l.set_knobs(S, rho)
 
     def time(self, mode, steps, warmup, hot=False):
-        """-> (mean us/step over exactly `steps` steps, per-round us list, host wall us/step).
-        hot: every step on the same copy of the weights (the last-level cache may serve them)."""
+        """-> (mean us/step over exactly `steps` steps, per-replay us/step list, host wall us/step).
+        hot: every step on the same copy of the weights (the last-level cache may serve them).
+        One HIP graph holds GRAPH_STEPS consecutive steps (several passes over the weight
+        copies), as a decoder's graph holds all its layers: a graph launch costs about 12 us
+        on this machine, which a graph of four steps would add as 3 us to every step."""
         torch = self.torch
         layers = self.layers[:1] * len(self.layers) if hot else self.layers
         n = len(layers)
+        per_graph = n * max(1, GRAPH_STEPS // n) if self.use_graph else n
+        seq = [layers[i % n] for i in range(per_graph)]
         with torch.cuda.stream(self.stream):
             for i in range(warmup):
                 self._call(layers[i % n], mode)
             self.stream.synchronize()
             graph = None
             if self.use_graph:
-                # one graph = one pass over all weight copies
                 graph = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(graph, stream=self.stream):
-                    for l in layers:
+                    for l in seq:
                         self._call(l, mode)
                 graph.replay()
                 self.stream.synchronize()
-            rounds, rem = divmod(steps, n)
+            rounds, rem = divmod(steps, per_graph)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(rounds + 2)]
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -129,16 +134,16 @@ class Runner:
                 if graph is not None:
                     graph.replay()
                 else:
-                    for l in layers:
+                    for l in seq:
                         self._call(l, mode)
                 ev[r + 1].record(self.stream)
             for i in range(rem):
-                self._call(layers[i], mode)
+                self._call(layers[i % n], mode)
             ev[rounds + 1].record(self.stream)
             torch.cuda.synchronize()
             wall = time.perf_counter() - t0
         total_ms = ev[0].elapsed_time(ev[rounds + 1])
-        per_round = [ev[r].elapsed_time(ev[r + 1]) * 1e3 / n for r in range(rounds)]
+        per_round = [ev[r].elapsed_time(ev[r + 1]) * 1e3 / per_graph for r in range(rounds)]
         return total_ms * 1e3 / steps, per_round, wall * 1e6 / steps
 
     def stage_times(self, mode, steps):
@@ -268,7 +273,7 @@ def main():
         "config": {"workload": spec.name, "tokens": spec.tokens, "hidden": spec.hidden,
                    "experts": spec.experts, "top_k": spec.top_k, "inter": spec.inter,
                    "shared": spec.shared, "select_top_k": args.S, "threshold": args.rho,
-                   "weight_copies": copies, "launch": "stream" if args.no_graph else "hip-graph",
+                   "weight_copies": copies, "launch": "stream" if args.no_graph else f"hip-graph of {GRAPH_STEPS} steps",
                    "similarity": "Frobenius estimate on the GPU (sere_similarity) from seeded calibration tokens"},
         "sere": sere, "no_reroute": base,
         "speedup_vs_no_reroute": round(base["us_per_step"] / sere["us_per_step"], 3),
