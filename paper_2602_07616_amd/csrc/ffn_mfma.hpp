@@ -30,6 +30,8 @@
 // E(x) = (silu(x W_gate) * (x W_up)) W_down.
 #pragma once
 
+#include <type_traits>
+
 #include "common.hpp"
 #include "ffn_generic.hpp"
 
@@ -274,52 +276,63 @@ __device__ __forceinline__ int start_rotation(int len, int chunk) {
 // h = silu(gate) * up is stored as bf16 (plus, if split_h, the bf16 rounding
 // residual in a second plane).
 // ---------------------------------------------------------------------------
-template <int NT, int KC, bool HALF>
+template <int NT, int KC, bool HALF, int NA = 1>
 __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W, int j0, int row0, int nrows,
                                              unsigned char* lds) {
+  static_assert(!HALF || NA == 1, "the half-tile layout has one tile per wavefront");
   const int lane = threadIdx.x & 63;
   const int i = lane & 15, g = lane >> 4;
   const int dh = p.dh, dm = p.dm;
   const int chunk = 2 * g + (i >> 3);
-  // HALF: the one half tile holds gate rows j0..j0+3 (tile rows 0-3) and up rows (tile rows 4-7)
-  const int xrow = HALF ? ((i & 4) ? dm + j0 + (i & 3) : j0 + (i & 3)) : j0 + (i & 7);
-  const uint16_t* wx[1] = {W + static_cast<size_t>(xrow) * dh + 8 * chunk};
-  const uint16_t* wy[1] = {W + static_cast<size_t>(dm + j0 + (i & 7)) * dh + 8 * chunk};
-  const TokenSource tok{static_cast<const uint16_t*>(p.hidden), p.sorted_token, row0, nrows, dh};
-  f32x4 acc[1][NT];
+  // HALF: the one half tile holds gate rows j0..j0+3 (tile rows 0-3) and up rows (tile rows 4-7);
+  // otherwise tile a holds gate rows j0 + 8a .. +7 (half tile X) and the matching up rows (Y)
+  const uint16_t* wx[NA];
+  const uint16_t* wy[NA];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) acc[0][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tiles<1, NT, KC, false, HALF>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC), lds, acc);
+  for (int a = 0; a < NA; ++a) {
+    const int xrow = HALF ? ((i & 4) ? dm + j0 + (i & 3) : j0 + (i & 3)) : j0 + 8 * a + (i & 7);
+    wx[a] = W + static_cast<size_t>(xrow) * dh + 8 * chunk;
+    wy[a] = W + static_cast<size_t>(dm + j0 + 8 * a + (i & 7)) * dh + 8 * chunk;
+  }
+  const TokenSource tok{static_cast<const uint16_t*>(p.hidden), p.sorted_token, row0, nrows, dh};
+  f32x4 acc[NA][NT];
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  stream_tiles<NA, NT, KC, false, HALF>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC), lds, acc);
 
   // gate values sit in lanes g < GL, the up values of the same (j, token) GL * 16 lanes higher
   constexpr int GL = HALF ? 1 : 2;
   uint16_t* h = reinterpret_cast<uint16_t*>(p.h);
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    f32x4 up;
+  for (int a = 0; a < NA; ++a)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) up[r] = __shfl(acc[0][t][r], (lane + 16 * GL) & 63, kWave);
-    const int n = t * kTile + i;
-    if (g < GL && n < nrows) {
-      uint16_t hi[4], lo[4];
+    for (int t = 0; t < NT; ++t) {
+      f32x4 up;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float hv = silu(acc[0][t][r]) * up[r];
-        hi[r] = f32_to_bf16(hv);
-        lo[r] = f32_to_bf16(hv - bf16_to_f32(hi[r]));
-      }
-      const size_t at = static_cast<size_t>(row0 + n) * dm + j0 + 4 * g;
-      uint2 packed;
-      packed.x = static_cast<uint32_t>(hi[0]) | (static_cast<uint32_t>(hi[1]) << 16);
-      packed.y = static_cast<uint32_t>(hi[2]) | (static_cast<uint32_t>(hi[3]) << 16);
-      *reinterpret_cast<uint2*>(h + at) = packed;
-      if (p.split_h) {
-        packed.x = static_cast<uint32_t>(lo[0]) | (static_cast<uint32_t>(lo[1]) << 16);
-        packed.y = static_cast<uint32_t>(lo[2]) | (static_cast<uint32_t>(lo[3]) << 16);
-        *reinterpret_cast<uint2*>(h + static_cast<size_t>(p.rows) * dm + at) = packed;
+      for (int r = 0; r < 4; ++r) up[r] = __shfl(acc[a][t][r], (lane + 16 * GL) & 63, kWave);
+      const int n = t * kTile + i;
+      if (g < GL && n < nrows) {
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float hv = silu(acc[a][t][r]) * up[r];
+          hi[r] = f32_to_bf16(hv);
+          lo[r] = f32_to_bf16(hv - bf16_to_f32(hi[r]));
+        }
+        const size_t at = static_cast<size_t>(row0 + n) * dm + j0 + 8 * a + 4 * g;
+        uint2 packed;
+        packed.x = static_cast<uint32_t>(hi[0]) | (static_cast<uint32_t>(hi[1]) << 16);
+        packed.y = static_cast<uint32_t>(hi[2]) | (static_cast<uint32_t>(hi[3]) << 16);
+        *reinterpret_cast<uint2*>(h + at) = packed;
+        if (p.split_h) {
+          packed.x = static_cast<uint32_t>(lo[0]) | (static_cast<uint32_t>(lo[1]) << 16);
+          packed.y = static_cast<uint32_t>(lo[2]) | (static_cast<uint32_t>(lo[3]) << 16);
+          *reinterpret_cast<uint2*>(h + static_cast<size_t>(p.rows) * dm + at) = packed;
+        }
       }
     }
-  }
 }
 
 // grid (dm / 16, max items), 256 threads: 4 wavefronts x 4 (fine) or 8 (coarse) intermediate indices
@@ -465,6 +478,70 @@ __global__ __launch_bounds__(256, 4) void ffn_down_mfma(FfnArgs p) {
       }
     }
   }
+}
+
+// ---------------------------------------------------------------------------
+// Prefill-sized batches (every expert has many token rows): the same building
+// blocks with squarer workgroup tiles.  Staging the token tile costs as much
+// traffic from L2 as the weights themselves once the tile holds 128 rows, so a
+// workgroup should cover as many weight rows per staged tile as it can hold
+// accumulators for: two tiles per wavefront and up to eight token tiles per
+// pass, at two workgroups per compute unit (the accumulators alone are 64
+// registers).  The host launches these kernels instead of the ones above when
+// the routing kernel cuts items of 128 rows; bf16 without the split h only.
+// ---------------------------------------------------------------------------
+constexpr int kWideGateUpJ = 16;  // intermediate indices per wavefront: two tiles of 8 gate + 8 up rows
+constexpr int kWideDownRows = 32; // output rows per wavefront: two tiles
+
+// k chunk per number of token tiles: the staged chunk must give each of the 256 threads a piece
+constexpr int wide_chunk(int nt) { return nt == 1 ? 256 : (nt == 2 ? 128 : 64); }
+
+template <int NA, bool GATEUP, typename Fn>
+__device__ __forceinline__ void wide_rows(int cnt, Fn&& pass) {
+  // rows of the item in passes of 128 while more than 64 remain, then one pass of <= 64, <= 32 or <= 16
+  int q = 0;
+  for (; cnt - q > 4 * kTile; q += 8 * kTile) pass(std::integral_constant<int, 8>{}, q, min(8 * kTile, cnt - q));
+  const int rem = cnt - q;
+  if (rem > 2 * kTile) {
+    pass(std::integral_constant<int, 4>{}, q, rem);
+  } else if (rem > kTile) {
+    pass(std::integral_constant<int, 2>{}, q, rem);
+  } else if (rem > 0) {
+    pass(std::integral_constant<int, 1>{}, q, rem);
+  }
+}
+
+// grid (dm / 64, max items), 256 threads
+__global__ __launch_bounds__(256, 2) void ffn_gateup_mfma_wide(FfnArgs p) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
+  const int w = blockIdx.y;
+  if (w >= *p.n_work) return;
+  const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
+  const uint16_t* W = static_cast<const uint16_t*>(
+      expert_base<SERE_BF16>(p.w_gate_up, p.shared_gate_up, e, p.M, static_cast<size_t>(2) * p.dm * p.dh));
+  const int j0 = (blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kWideGateUpJ;
+  wide_rows<2, true>(cnt, [&](auto nt, int q, int n) {
+    constexpr int NT = decltype(nt)::value;
+    gateup_group<NT, wide_chunk(NT), false, 2>(p, W, j0, off + q, n, lds);
+  });
+}
+
+// grid (ceil(dh / 128) * ksplit, max items), 256 threads
+__global__ __launch_bounds__(256, 2) void ffn_down_mfma_wide(FfnArgs p) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
+  const int w = blockIdx.y;
+  if (w >= *p.n_work) return;
+  const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
+  const uint16_t* W = static_cast<const uint16_t*>(
+      expert_base<SERE_BF16>(p.w_down, p.shared_down, e, p.M, static_cast<size_t>(p.dh) * p.dm));
+  const int slab = blockIdx.x / p.ksplit, slice = blockIdx.x % p.ksplit;
+  const int r0 = (slab * kWavesPerBlock + (threadIdx.x >> 6)) * kWideDownRows;
+  const int blocks = p.dm >> 6, per = (blocks + p.ksplit - 1) / p.ksplit;
+  const int kbeg = min(slice * per, blocks) << 6, kend = min((slice + 1) * per, blocks) << 6;
+  wide_rows<2, false>(cnt, [&](auto nt, int q, int n) {
+    constexpr int NT = decltype(nt)::value;
+    down_group<2, NT, wide_chunk(NT), false>(p, W, r0, kbeg, kend, slice, off + q, n, lds);
+  });
 }
 
 }  // namespace sere

@@ -293,9 +293,19 @@ static void launch_combine(const sere_config& c, const Layout& l, const Pointers
     launch_stage(SERE_STAGE_COMBINE, s, combine_kernel<SERE_BF16>, grid, dim3(256), ca);
 }
 
-// fp32 layers: vector-ALU kernels.  bf16 layers: matrix-core kernels.
+// fp32 layers: vector-ALU kernels.  bf16 layers: matrix-core kernels; `wide`: the variants for
+// batches whose work items hold 128 rows (prefill-sized).
 static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, int ksplit, const FfnArgs& f,
-                               hipStream_t s) {
+                               hipStream_t s, bool wide = false) {
+  if (dtype == SERE_BF16 && wide) {
+    launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_mfma_wide, dim3(inter / (kWideGateUpJ * kWavesPerBlock), max_work),
+                 dim3(256), f);
+    launch_stage(SERE_STAGE_DOWN, s, ffn_down_mfma_wide,
+                 dim3(((hidden + kWideDownRows * kWavesPerBlock - 1) / (kWideDownRows * kWavesPerBlock)) * ksplit,
+                      max_work),
+                 dim3(256), f);
+    return;
+  }
   if (dtype == SERE_F32) {
     launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_generic<SERE_F32>, dim3((inter + kGenJB - 1) / kGenJB, max_work),
                  dim3(256), f);
@@ -312,7 +322,8 @@ static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, i
 
 static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
                        hipStream_t s) {
-  launch_gateup_down(c.dtype, c.inter, c.hidden, l.max_work, l.ksplit, f, s);
+  const bool wide = c.dtype == SERE_BF16 && !f.split_h && p.route.item_rows == 4 * kItemRows;
+  launch_gateup_down(c.dtype, c.inter, c.hidden, l.max_work, l.ksplit, f, s, wide);
   launch_combine(c, l, p, f.hidden, out, s);
 }
 
