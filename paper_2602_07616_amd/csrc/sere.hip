@@ -322,7 +322,7 @@ static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, i
 
 static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
                        hipStream_t s) {
-  const bool wide = c.dtype == SERE_BF16 && !f.split_h && p.route.item_rows == 4 * kItemRows;
+  const bool wide = c.dtype == SERE_BF16 && !f.split_h && p.route.item_rows >= 2 * kItemRows;
   launch_gateup_down(c.dtype, c.inter, c.hidden, l.max_work, l.ksplit, f, s, wide);
   launch_combine(c, l, p, f.hidden, out, s);
 }
