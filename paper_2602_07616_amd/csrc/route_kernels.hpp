@@ -266,28 +266,36 @@ __device__ __forceinline__ double group_sum(double v) {
   return v;
 }
 
-template <int LP, int KS>
+// KEEP (8 or 16, >= min(K, 16)): list entries held per lane; a sorted list cannot
+// contribute more than K entries to the top K, so for K <= 8 half a list is enough.
+template <int LP, int KS, int KEEP>
 __device__ __forceinline__ void topk_merge(const uint64_t* __restrict__ list_key,
                                            const uint8_t* __restrict__ list_id, bool active, int nlists,
                                            int32_t* __restrict__ ids, float* __restrict__ w, uint8_t* ids8, int K) {
   const int l = threadIdx.x & (LP - 1);
   const bool has_list = active && l < nlists;
-  uint64_t key[16];
-  uint32_t idw[4];  // 16 expert ids, one byte each
+  static_assert(KEEP == 8 || KEEP == 16, "half a list or a whole one");
+  uint64_t key[KEEP];
+  uint32_t idw[4];  // expert ids, one byte each (the upper two words stay 0 for KEEP == 8)
+  idw[0] = idw[1] = idw[2] = idw[3] = 0;
   if (has_list) {
     const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(list_key + static_cast<size_t>(l) * 16);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < KEEP / 2; ++j) {
       const ulonglong2 v = kp[j];
       key[2 * j] = v.x;
       key[2 * j + 1] = v.y;
     }
-    const uint4 iv = *reinterpret_cast<const uint4*>(list_id + static_cast<size_t>(l) * 16);
-    idw[0] = iv.x; idw[1] = iv.y; idw[2] = iv.z; idw[3] = iv.w;
+    if (KEEP == 16) {
+      const uint4 iv = *reinterpret_cast<const uint4*>(list_id + static_cast<size_t>(l) * 16);
+      idw[0] = iv.x; idw[1] = iv.y; idw[2] = iv.z; idw[3] = iv.w;
+    } else {
+      const uint2 iv = *reinterpret_cast<const uint2*>(list_id + static_cast<size_t>(l) * 16);
+      idw[0] = iv.x; idw[1] = iv.y;
+    }
   } else {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) key[j] = 0;
-    idw[0] = idw[1] = idw[2] = idw[3] = 0;
+    for (int j = 0; j < KEEP; ++j) key[j] = 0;
   }
   double mysel[KS];
 #pragma unroll
@@ -303,8 +311,8 @@ __device__ __forceinline__ void topk_merge(const uint64_t* __restrict__ list_key
     // every lane of the group now holds the winner; its owner pops
     if (key[0] != 0 && (idw[0] & 0xffu) == wid) {
 #pragma unroll
-      for (int j = 0; j < 15; ++j) key[j] = key[j + 1];
-      key[15] = 0;
+      for (int j = 0; j < KEEP - 1; ++j) key[j] = key[j + 1];
+      key[KEEP - 1] = 0;
       idw[0] = (idw[0] >> 8) | (idw[1] << 24);
       idw[1] = (idw[1] >> 8) | (idw[2] << 24);
       idw[2] = (idw[2] >> 8) | (idw[3] << 24);
@@ -628,8 +636,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteArgs p) {
 // the workgroup that takes the last ticket.  With a single workgroup there is
 // no ticket and the ids go from the top-K to the batch-wide step through LDS.
 // grid ceil(T*LP/1024), 1024 threads; *ticket must be 0 at launch.
-// LP = lanes per token >= number of lists (4, 8, 16); K <= KS*LP.
-template <int LP, int KS>
+// LP = lanes per token >= number of lists (4, 8, 16); K <= KS*LP; KEEP >= min(K, 16).
+template <int LP, int KS, int KEEP>
 __global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const uint64_t* __restrict__ list_key,
                                                                    const uint8_t* __restrict__ list_id,
                                                                    int32_t* __restrict__ topk_ids,
@@ -647,7 +655,7 @@ __global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const uint64_
   const int first_of_wave = blockIdx.x * kTokens + (threadIdx.x >> 6) * (kWave / LP);
   if (first_of_wave < p.T) {  // wave-uniform: the wavefront has a token
     const size_t tt = has ? t : 0;
-    topk_merge<LP, KS>(list_key + tt * nlists * 16, list_id + tt * nlists * 16, has, nlists, topk_ids + tt * p.K,
+    topk_merge<LP, KS, KEEP>(list_key + tt * nlists * 16, list_id + tt * nlists * 16, has, nlists, topk_ids + tt * p.K,
                        topk_w + tt * p.K, lone ? s.ids8 + tt * p.K : nullptr, p.K);
   }
   if (lone) {

@@ -261,15 +261,20 @@ static int launch_route(const sere_config& c, const Pointers& p, bool with_topk,
     const int lp = lists <= 4 ? 4 : (lists <= 8 ? 8 : 16);
     const bool small_k = c.top_k <= 2 * lp;
     const dim3 grid((c.num_tokens * lp + kRouteThreads - 1) / kRouteThreads);
-#define SERE_LAUNCH_TOPK(LP, KS)                                                                                \
-  launch_stage(SERE_STAGE_ROUTE, s, topk_route_kernel<LP, KS>, grid, dim3(kRouteThreads), p.list_key, p.list_id, \
-               p.topk_ids, p.topk_w, p.ticket, p.route)
+#define SERE_LAUNCH_TOPK(LP, KS, KEEP)                                                                          \
+  launch_stage(SERE_STAGE_ROUTE, s, topk_route_kernel<LP, KS, KEEP>, grid, dim3(kRouteThreads), p.list_key, \
+               p.list_id, p.topk_ids, p.topk_w, p.ticket, p.route)
+    const bool half_lists = c.top_k <= 8;  // no list can give more than K entries
     if (lp == 4) {
-      if (small_k) SERE_LAUNCH_TOPK(4, 2); else SERE_LAUNCH_TOPK(4, 16);
+      if (small_k) SERE_LAUNCH_TOPK(4, 2, 8); else SERE_LAUNCH_TOPK(4, 16, 16);
     } else if (lp == 8) {
-      if (small_k) SERE_LAUNCH_TOPK(8, 2); else SERE_LAUNCH_TOPK(8, 16);
+      if (half_lists) SERE_LAUNCH_TOPK(8, 2, 8);
+      else if (small_k) SERE_LAUNCH_TOPK(8, 2, 16);
+      else SERE_LAUNCH_TOPK(8, 16, 16);
     } else {
-      if (small_k) SERE_LAUNCH_TOPK(16, 2); else SERE_LAUNCH_TOPK(16, 16);
+      if (half_lists) SERE_LAUNCH_TOPK(16, 2, 8);
+      else if (small_k) SERE_LAUNCH_TOPK(16, 2, 16);
+      else SERE_LAUNCH_TOPK(16, 16, 16);
     }
 #undef SERE_LAUNCH_TOPK
   } else {
