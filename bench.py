@@ -32,9 +32,9 @@ GRAPH_STEPS = 32          # decode steps captured in one HIP graph (see Runner.t
 # WRITE_SIZE x 1.0000); commands and tables: profiles/sere_step_<workload>.md.  Keyed by
 # (workload, select_top_k, threshold); other configurations report null.
 MEASURED_TRAFFIC = {
-    ("qwen3_b32", 2, 0.0): {"gate_up": 204660005, "down": 106605993},
-    ("qwen3_b128", 2, 0.0): {"gate_up": 661108337, "down": 350124011},
-    ("mixtral_b64", 2, 0.0): {"gate_up": 1890645979, "down": 1061036283},
+    ("qwen3_b32", 2, 0.0): {"gate_up": 204335652, "down": 106599894},
+    ("qwen3_b128", 2, 0.0): {"gate_up": 660773920, "down": 350131729},
+    ("mixtral_b64", 2, 0.0): {"gate_up": 1890675817, "down": 1060992118},
 }
 
 
