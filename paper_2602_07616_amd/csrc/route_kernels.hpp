@@ -109,7 +109,8 @@ __device__ __forceinline__ void rank_step(uint64_t key, uint32_t id, uint32_t& r
 template <int DT>
 __global__ __launch_bounds__(256) void router_logits_kernel(
     const void* __restrict__ hidden, const void* __restrict__ router_w, uint64_t* __restrict__ list_key,
-    uint8_t* __restrict__ list_id, int T, int M, int dh, int32_t* clear_word) {
+    uint8_t* __restrict__ list_id, int /*T: one workgroup row per token, see grid*/, int M, int dh,
+    int32_t* clear_word) {
   __shared__ double s_logit[16];
   const int t = blockIdx.y;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
