@@ -103,6 +103,11 @@ class DeviceLayer:
         B.sere_route(self.cfg, self.hidden, self.router_w, self.sim,
                      self.route if with_outputs else None, self.workspace, stream)
 
+    def run_reroute(self, stream=None, with_outputs=True) -> None:
+        """Re-routing alone on the top-K ids of the last run with outputs (indices in, indices out)."""
+        B.sere_reroute(self.cfg, self.route.topk_ids, self.sim, self.route if with_outputs else None,
+                       self.workspace, stream)
+
     def run_decode(self, stream=None, with_outputs=True) -> None:
         B.sere_moe_decode(self.cfg, self.hidden, self.router_w, self.w_gate_up, self.w_down,
                           self.shared_gate_up, self.shared_down, self.sim, self.out,
