@@ -218,6 +218,27 @@ def test_prefill_sized_batch(dev):
         check_output(layer.out_to_host_f64()[tokens], want, wl.spec.dtype, f"T={T} S={S}")
 
 
+def test_non_power_of_two_layer_at_full_size(dev):
+    """d_h = 2880 and d_m = 1472 (45 and 23 blocks of 64): the last k chunk of every row and the
+    last row block of the down projection are partial; 32 experts, 48 tokens, one shared expert.
+    Integers for the whole batch, outputs on sampled tokens, with and without re-routing."""
+    spec = wk.custom_spec("odd2880", wk.BF16, 2880, 32, 4, 1472, 1, 48, 5150, clusters=4, twin_src=0,
+                          twin_dst=16, twin_n=16, calib_batches=1, calib_tokens=8)
+    wl = wk.make_workload(spec)
+    sim = pins.rand_sim(5150, spec.experts)
+    layer = dev.DeviceLayer.from_workload(wl, sim, 1, 0.3)
+    tokens = [0, 5, 17, 23, 31, 40, 47]
+    for S, rho in ((1, 0.3), (2, 0.0), (4, 0.0)):
+        print(f"odd shape S={S} rho={rho}", flush=True)
+        layer.set_knobs(S, rho)
+        layer.run_decode()
+        ref = oracle.route(wl.hidden, wl.router_w, spec.dtype, spec.top_k, sim, S, rho)
+        assert ref.min_gap > 1e-9
+        check_routing(layer.routing_to_host(), ref, layer.cfg)
+        want = oracle_output(wl, ref.rerouted_ids, ref.topk_weights, "odd2880", tokens)
+        check_output(layer.out_to_host_f64()[tokens], want, spec.dtype, f"odd shape S={S}")
+
+
 # ------------------------------------------------------------ edge cases ---
 def small_case(dev, dtype, T, dh, M, K, dm, n_sh, seed, S, rho, sim=None, mutate=None):
     spec = wk.custom_spec(f"edge{seed}", dtype, dh, M, K, dm, n_sh, T, seed, weight_std=0.02,
