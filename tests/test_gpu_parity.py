@@ -450,6 +450,18 @@ def test_similarity_cosine_parity(dev, name):
         assert min(twins) > 0.9 and np.abs(got - np.eye(sp.experts)).max() > 0.9
 
 
+def test_similarity_with_long_calibration_batches(dev):
+    """100 calibration tokens per batch: every expert is a work item of 100 rows, served in passes of
+    up to 128 (gate/up) and 64 (down) token rows."""
+    spec = wk.custom_spec("cal100", wk.BF16, 256, 12, 2, 192, 0, 4, 6100, twin_src=0, twin_dst=6, twin_n=6,
+                          calib_batches=2, calib_tokens=100)
+    wl = wk.make_workload(spec)
+    for metric, ref in (("frobenius", oracle.similarity_frobenius), ("cosine", oracle.similarity_cosine)):
+        got = dev.similarity_on_device(wl, metric=metric).cpu().numpy()
+        want = ref(wl.calib, wl.w_gate_up, wl.w_down, spec.dtype)
+        assert np.abs(got - want).max() <= 5e-3, (metric, np.abs(got - want).max())
+
+
 def test_similarity_feeds_routing(dev):
     """The library's own similarity matrix drives the same re-routing as the
     oracle's on the tiny fp32 layer (values agree to 1e-5 and no two candidate
