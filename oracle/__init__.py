@@ -204,6 +204,23 @@ class OracleLib:
                                         dh, M, dm, _p(act), _p(sim))
         return sim
 
+    def similarity_cka_linear(self, calib, w_gate_up, w_down, dtype: int) -> np.ndarray:
+        """-> S [M,M] float64, linear-kernel CKA with the unbiased HSIC estimator (appendix on
+        similarity metrics); needs at least 4 tokens per calibration batch."""
+        calib = _check(calib, dtype)
+        w_gate_up, w_down = _check(w_gate_up, dtype), _check(w_down, dtype)
+        N, n, dh = calib.shape
+        M, dm2, _ = w_gate_up.shape
+        dm = dm2 // 2
+        assert n >= 4
+        assert w_gate_up.shape == (M, 2 * dm, dh) and w_down.shape == (M, dh, dm)
+        act = np.empty((M, n, dh), dtype=np.float64)
+        gram = np.empty((M, n, n), dtype=np.float64)
+        sim = np.empty((M, M), dtype=np.float64)
+        self.c.oracle_similarity_cka_linear(_p(calib), _p(w_gate_up), _p(w_down), dtype, N, n,
+                                            dh, M, dm, _p(act), _p(gram), _p(sim))
+        return sim
+
     def route(self, hidden, router_w, dtype: int, K: int, sim, S: int,
               rho: float) -> LayerResult:
         """Routing half of the layer (no expert is executed)."""

@@ -469,3 +469,89 @@ void oracle_similarity_cosine(const void *calib, const void *w_gate_up, const vo
         sim[i] = sim[i] / (double)N;
     free(norm);
 }
+
+/*
+ * Expert-similarity matrix with linear-kernel CKA (appendix "Centered Kernel
+ * Alignment"): for each calibration batch and expert j the n x n Gram matrix
+ * K_j = A_j A_j^T of its outputs A_j = E_j(X) [n][dh];
+ *   CKA(p,q) = HSIC(K_p,K_q) / sqrt(HSIC(K_p,K_p) HSIC(K_q,K_q)),
+ * with the unbiased estimator of HSIC (the appendix names it and refers to the
+ * literature for the formula; reading of this build: the estimator of Song et
+ * al. 2012, the one minibatch CKA uses): with Kt, Lt = K, L with their
+ * diagonals set to zero and 1 the all-ones vector,
+ *   HSIC(K,L) = [ tr(Kt Lt) + (1'Kt1)(1'Lt1)/((n-1)(n-2)) - 2 (1'Kt Lt 1)/(n-2) ]
+ *               / (n (n-3)),                                   n >= 4.
+ * S[p][q] += CKA(p,q) per batch, finally S /= N (Sec. 3.1.1).  If either
+ * self-term is not positive the quotient is undefined and the pair contributes
+ * 0 (reading of this build).  act: caller scratch of M*n*dh doubles; gram:
+ * caller scratch of M*n*n doubles.
+ */
+static double hsic_unbiased(const double *Kt, const double *Lt, int n)
+{
+    double tr = 0.0, sk = 0.0, sl = 0.0, cross = 0.0;
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) {
+            tr += Kt[(size_t)i * n + j] * Lt[(size_t)j * n + i];
+            sk += Kt[(size_t)i * n + j];
+            sl += Lt[(size_t)i * n + j];
+        }
+    for (int j = 0; j < n; ++j) {
+        double col_k = 0.0, row_l = 0.0; /* (1'Kt)_j and (Lt 1)_j */
+        for (int i = 0; i < n; ++i) {
+            col_k += Kt[(size_t)i * n + j];
+            row_l += Lt[(size_t)j * n + i];
+        }
+        cross += col_k * row_l;
+    }
+    double dn = (double)n;
+    return (tr + sk * sl / ((dn - 1.0) * (dn - 2.0)) - 2.0 * cross / (dn - 2.0)) / (dn * (dn - 3.0));
+}
+
+void oracle_similarity_cka_linear(const void *calib, const void *w_gate_up, const void *w_down,
+                                  int dtype, int N, int n, int dh, int M, int dm, double *act,
+                                  double *gram, double *sim)
+{
+    size_t gu = (size_t)2 * dm * dh, dn = (size_t)dh * dm;
+    double *self = (double *)malloc(sizeof(double) * (size_t)M);
+    for (size_t i = 0; i < (size_t)M * M; ++i)
+        sim[i] = 0.0;
+    for (int b = 0; b < N; ++b) {
+#pragma omp parallel
+        {
+            double *scratch = (double *)malloc(sizeof(double) * (size_t)dm);
+#pragma omp for schedule(dynamic, 1) collapse(2)
+            for (int j = 0; j < M; ++j)
+                for (int r = 0; r < n; ++r)
+                    expert_ffn(elem_ptr(calib, dtype, ((size_t)b * n + r) * dh),
+                               elem_ptr(w_gate_up, dtype, (size_t)j * gu),
+                               elem_ptr(w_down, dtype, (size_t)j * dn), dtype, dh, dm,
+                               scratch, act + ((size_t)j * n + r) * dh);
+            free(scratch);
+        }
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int j = 0; j < M; ++j)
+            for (int r = 0; r < n; ++r)
+                for (int c = 0; c < n; ++c) {
+                    const double *x = act + ((size_t)j * n + r) * dh;
+                    const double *y = act + ((size_t)j * n + c) * dh;
+                    double dot = 0.0;
+                    for (int k = 0; k < dh; ++k)
+                        dot += x[k] * y[k];
+                    gram[((size_t)j * n + r) * n + c] = (r == c) ? 0.0 : dot;
+                }
+        for (int j = 0; j < M; ++j)
+            self[j] = hsic_unbiased(gram + (size_t)j * n * n, gram + (size_t)j * n * n, n);
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int p = 0; p < M; ++p)
+            for (int q = 0; q < M; ++q) {
+                double cka = 0.0;
+                if (self[p] > 0.0 && self[q] > 0.0)
+                    cka = hsic_unbiased(gram + (size_t)p * n * n, gram + (size_t)q * n * n, n) /
+                          sqrt(self[p] * self[q]);
+                sim[(size_t)p * M + q] += cka;
+            }
+    }
+    for (size_t i = 0; i < (size_t)M * M; ++i)
+        sim[i] = sim[i] * (1.0 / (double)N);
+    free(self);
+}

@@ -5,6 +5,7 @@ never with the oracle itself.  Every check takes the oracle object ``o`` so the
 same checks can be pointed at deliberately broken builds of the oracle
 (tests/test_oracle_mutants.py) to show that each plausible mistake is caught.
 """
+import itertools
 import json
 import math
 import os
@@ -516,7 +517,62 @@ def pin_similarity_cosine(o):
     assert np.all(s[1] == 0.0) and np.all(s[:, 1] == 0.0) and abs(s[0, 0] - 1.0) < 1e-14
 
 
+def _hsic_ustatistic(K, L):
+    """Unbiased HSIC as the U-statistic it is defined as (Song et al. 2012): the mean, over all
+    ordered 4-tuples (s, t, u, v) of distinct indices, of K_st (L_st + L_uv - 2 L_su).  O(n^4)."""
+    n = K.shape[0]
+    total, count = 0.0, 0
+    for s_, t_, u_, v_ in itertools.permutations(range(n), 4):
+        total += K[s_, t_] * (L[s_, t_] + L[u_, v_] - 2.0 * L[s_, u_])
+        count += 1
+    return total / count
+
+
+def pin_similarity_cka(o):
+    """Linear CKA with the unbiased HSIC estimator: brute force over 4-tuples on tiny batches, the
+    invariances the appendix states (isotropic scaling, orthogonal transformations), twins."""
+    for dtype, seed in ((wk.F32, 121), (wk.BF16, 122)):
+        c = rng_case(seed, dtype, 1, 24, 5, 10)
+        c["w_gate_up"][4] = c["w_gate_up"][2]
+        c["w_down"][4] = c["w_down"][2]                       # exact twin of expert 2
+        cal = wk.to_storage(wk.std_normal(seed, "cal", 2 * 6 * 24), dtype).reshape(2, 6, 24)
+        s = o.similarity_cka_linear(cal, c["w_gate_up"], c["w_down"], dtype)
+        N, M = cal.shape[0], c["w_gate_up"].shape[0]
+        want = np.zeros((M, M))
+        for b in range(N):
+            acts = [np_expert(f64(cal[b], dtype), f64(c["w_gate_up"][e], dtype), f64(c["w_down"][e], dtype))
+                    for e in range(M)]
+            grams = [a @ a.T for a in acts]
+            h = np.array([[_hsic_ustatistic(grams[p], grams[q]) for q in range(M)] for p in range(M)])
+            want += h / np.sqrt(np.outer(np.diag(h), np.diag(h)))
+        want /= N
+        assert np.allclose(s, want, rtol=1e-9, atol=1e-11), np.abs(s - want).max()
+        assert np.allclose(s, s.T, rtol=0, atol=1e-13)
+        assert np.allclose(np.diag(s), 1.0, atol=1e-13)
+        assert abs(s[2, 4] - 1.0) < 1e-13
+    # invariances: expert 1 = 0.5 x expert 0 (isotropic scaling), expert 2 = expert 0 followed by an
+    # orthogonal map of the output space; expert 3 independent
+    c = rng_case(123, wk.F32, 1, 16, 4, 6)
+    q_mat, _ = np.linalg.qr(wk.std_normal(123, "q", 16 * 16).reshape(16, 16))
+    c["w_gate_up"][1] = c["w_gate_up"][0]
+    c["w_down"][1] = np.float32(0.5) * c["w_down"][0]
+    c["w_gate_up"][2] = c["w_gate_up"][0]
+    c["w_down"][2] = (q_mat @ c["w_down"][0].astype(np.float64)).astype(np.float32)
+    cal = wk.std_normal(123, "cal", 2 * 7 * 16).reshape(2, 7, 16)
+    s = o.similarity_cka_linear(cal, c["w_gate_up"], c["w_down"], wk.F32)
+    assert abs(s[0, 1] - 1.0) < 1e-12
+    assert abs(s[0, 2] - 1.0) < 1e-5          # the rotated weights were rounded to fp32
+    assert abs(s[0, 3]) < 0.98
+    # an expert with zero output: HSIC of its Gram matrix is 0, every pair with it contributes 0
+    c = rng_case(124, wk.F32, 1, 16, 3, 4)
+    c["w_down"][1] = 0
+    cal = wk.std_normal(124, "cal", 5 * 16).reshape(1, 5, 16)
+    s = o.similarity_cka_linear(cal, c["w_gate_up"], c["w_down"], wk.F32)
+    assert np.all(s[1] == 0.0) and np.all(s[:, 1] == 0.0) and abs(s[0, 0] - 1.0) < 1e-13
+
+
 ALL_PINS = [
+    pin_similarity_cka,
     pin_similarity_cosine,
     pin_router_logits_library, pin_topk_order_and_gate, pin_fig2_behaviour,
     pin_reroute_hand_cases, pin_reroute_against_brute, pin_reroute_invariants, pin_compact,

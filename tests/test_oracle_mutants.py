@@ -58,6 +58,13 @@ MUTANTS = [
     ("cosine_norm_no_sqrt", "norm[(size_t)j * n + r] = sqrt(ss);", "norm[(size_t)j * n + r] = ss;",
      [pins.pin_similarity_cosine]),
     ("cosine_not_averaged", "sim[i] = sim[i] / (double)N;", "sim[i] = sim[i];", [pins.pin_similarity_cosine]),
+    ("cka_diagonal_kept", "(r == c) ? 0.0 : dot;", "dot;", [pins.pin_similarity_cka]),
+    ("cka_cross_term_sign", "- 2.0 * cross / (dn - 2.0)", "+ 2.0 * cross / (dn - 2.0)", [pins.pin_similarity_cka]),
+    ("cka_cross_term_weight", "- 2.0 * cross / (dn - 2.0)", "- 2.0 * cross / (dn - 1.0)", [pins.pin_similarity_cka]),
+    ("cka_sum_term_weight", "sk * sl / ((dn - 1.0) * (dn - 2.0))", "sk * sl / (dn * dn)", [pins.pin_similarity_cka]),
+    ("cka_sum_term_dropped", "tr + sk * sl / ((dn - 1.0) * (dn - 2.0))", "tr", [pins.pin_similarity_cka]),
+    ("cka_no_sqrt", "sqrt(self[p] * self[q]);", "(self[p] * self[q]);", [pins.pin_similarity_cka]),
+    ("cka_not_averaged", "sim[i] = sim[i] * (1.0 / (double)N);", "sim[i] = sim[i];", [pins.pin_similarity_cka]),
 ]
 
 
