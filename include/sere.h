@@ -51,7 +51,8 @@ extern "C" {
 #define SERE_ERR_BAD_DTYPE (-4)           /* dtype is neither SERE_F32 nor SERE_BF16     */
 #define SERE_ERR_MISALIGNED (-5)          /* a pointer is not 16-byte aligned            */
 #define SERE_ERR_WORKSPACE_TOO_SMALL (-6) /* workspace_bytes < sere_workspace_bytes()    */
-#define SERE_ERR_BAD_FLAGS (-7)           /* flags has a bit no SERE_FLAG_* names        */
+#define SERE_ERR_BAD_FLAGS (-7)           /* flags has a bit no SERE_FLAG_* names, or two
+                                             that exclude each other                     */
 #define SERE_ERR_NONFINITE_THRESHOLD (-8) /* threshold is NaN or infinite                */
 #define SERE_ERR_HIP (-9)                 /* a HIP launch reported an error              */
 
@@ -64,6 +65,9 @@ extern "C" {
 #define SERE_FLAG_SIM_COSINE 2 /* sere_similarity: the cosine metric instead of the Frobenius one
                                  (appendix on similarity metrics); ignored by the other entry
                                  points                                                        */
+#define SERE_FLAG_SIM_CKA_LINEAR 4 /* sere_similarity: linear-kernel CKA instead (same appendix);
+                                     excludes SERE_FLAG_SIM_COSINE; ignored by the other entry
+                                     points                                                    */
 
 #define SERE_MAX_EXPERTS 256
 #define SERE_MAX_SHARED 16
@@ -197,7 +201,15 @@ int sere_moe_decode_baseline(const sere_config *cfg, const void *hidden, const v
  * appendix "Cosine Similarity" instead: Sim(p,q) = the mean over the batch's
  * tokens of the cosine between the two experts' outputs for that token (a
  * token where either output is the zero vector contributes 0); values lie in
- * [-1, 1].
+ * [-1, 1].  With SERE_FLAG_SIM_CKA_LINEAR it is centered kernel alignment with
+ * the linear kernel (appendix "Centered Kernel Alignment"): K_p = A_p A_p^T
+ * [batch_tokens, batch_tokens] per expert, Sim(p,q) = HSIC(K_p,K_q) /
+ * sqrt(HSIC(K_p,K_p) HSIC(K_q,K_q)) with the unbiased O(n^2) estimator of HSIC
+ * that the appendix refers to (on the Gram matrices with zeroed diagonals Kt:
+ * [tr(Kt_p Kt_q) + (1'Kt_p 1)(1'Kt_q 1)/((n-1)(n-2)) - 2 (1'Kt_p Kt_q 1)/(n-2)]
+ * / (n(n-3))); a pair with a non-positive self-term contributes 0; needs
+ * 4 <= batch_tokens <= 512 (else SERE_ERR_BAD_SHAPE).  The RBF and polynomial
+ * kernels of that appendix are not built (their parameters are not given).
  *   calib [num_batches, batch_tokens, d_h]  dtype, device
  *   sim   [M, M] fp32, device, written
  * Uses cfg->hidden, num_experts, inter, dtype (the other fields must be valid

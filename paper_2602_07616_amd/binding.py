@@ -15,6 +15,7 @@ SERE_BF16 = 1
 
 SERE_FLAG_RESIDUAL = 1
 SERE_FLAG_SIM_COSINE = 2
+SERE_FLAG_SIM_CKA_LINEAR = 4
 
 SERE_OK = 0
 SERE_ERR_NULL_PTR = -1

@@ -76,7 +76,8 @@ static Layout make_layout(const sere_config& c) {
 static int check_config(const sere_config* c) {
   if (c == nullptr) return SERE_ERR_NULL_PTR;
   if (c->dtype != SERE_F32 && c->dtype != SERE_BF16) return SERE_ERR_BAD_DTYPE;
-  if ((c->flags & ~(SERE_FLAG_RESIDUAL | SERE_FLAG_SIM_COSINE)) != 0) return SERE_ERR_BAD_FLAGS;
+  if ((c->flags & ~(SERE_FLAG_RESIDUAL | SERE_FLAG_SIM_COSINE | SERE_FLAG_SIM_CKA_LINEAR)) != 0) return SERE_ERR_BAD_FLAGS;
+  if ((c->flags & SERE_FLAG_SIM_COSINE) && (c->flags & SERE_FLAG_SIM_CKA_LINEAR)) return SERE_ERR_BAD_FLAGS;
   if (c->num_tokens < 1 || c->num_tokens > SERE_MAX_TOKENS) return SERE_ERR_BAD_SHAPE;
   if (c->hidden < 64 || c->hidden % 64 != 0 || c->hidden > (1 << 16)) return SERE_ERR_BAD_SHAPE;
   if (c->inter < 64 || c->inter % 64 != 0 || c->inter > (1 << 18)) return SERE_ERR_BAD_SHAPE;
@@ -401,7 +402,7 @@ static int decode(const sere_config* cfg, const void* hidden, const void* router
 
 // ------------------------------------------------------------- similarity ---
 struct SimLayout {
-  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, total;
+  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, gram, rowsum, total;
   int rows, ksplit;
 };
 
@@ -425,12 +426,19 @@ static SimLayout make_sim_layout(const sere_config& c, int n) {
   l.y = take(static_cast<size_t>(l.ksplit) * R * c.hidden * sizeof(float));
   l.dist = take(M * M * sizeof(double));
   l.acc = take(M * M * sizeof(double));
+  if (c.flags & SERE_FLAG_SIM_CKA_LINEAR) {  // Gram matrix and its row sums per expert
+    l.gram = take(R * n * sizeof(double));
+    l.rowsum = take(R * sizeof(double));
+  }
   l.total = o;
   return l;
 }
 
-static int check_similarity_sizes(int32_t num_batches, int32_t n) {
+constexpr int kCkaMinTokens = 4, kCkaMaxTokens = 512;  // the estimator's lower limit; M*n*n doubles of workspace
+
+static int check_similarity_sizes(const sere_config& c, int32_t num_batches, int32_t n) {
   if (num_batches < 1 || num_batches > 4096 || n < 1 || n > 4096) return SERE_ERR_BAD_SHAPE;
+  if ((c.flags & SERE_FLAG_SIM_CKA_LINEAR) && (n < kCkaMinTokens || n > kCkaMaxTokens)) return SERE_ERR_BAD_SHAPE;
   return SERE_OK;
 }
 
@@ -508,7 +516,7 @@ int sere_moe_decode_baseline(const sere_config* cfg, const void* hidden, const v
 }
 
 size_t sere_similarity_workspace_bytes(const sere_config* cfg, int32_t batch_tokens) {
-  if (check_config(cfg) != SERE_OK || check_similarity_sizes(1, batch_tokens) != SERE_OK) return 0;
+  if (check_config(cfg) != SERE_OK || check_similarity_sizes(*cfg, 1, batch_tokens) != SERE_OK) return 0;
   return make_sim_layout(*cfg, batch_tokens).total;
 }
 
@@ -517,7 +525,7 @@ int sere_similarity(const sere_config* cfg, const void* calib, int32_t num_batch
                     size_t workspace_bytes, void* hip_stream) {
   int st = check_config(cfg);
   if (st != SERE_OK) return st;
-  st = check_similarity_sizes(num_batches, batch_tokens);
+  st = check_similarity_sizes(*cfg, num_batches, batch_tokens);
   if (st != SERE_OK) return st;
   PtrCheck pc;
   pc.need(calib);
@@ -557,18 +565,27 @@ int sere_similarity(const sere_config* cfg, const void* calib, int32_t num_batch
                      const_cast<int32_t*>(f.work_off), const_cast<int32_t*>(f.work_cnt),
                      const_cast<int32_t*>(f.n_work));
   const size_t eb = cfg->dtype == SERE_F32 ? 4 : 2;
-  const int cosine = (cfg->flags & SERE_FLAG_SIM_COSINE) ? 1 : 0;
+  const int metric = (cfg->flags & SERE_FLAG_SIM_COSINE)
+                         ? kMetricCosine
+                         : ((cfg->flags & SERE_FLAG_SIM_CKA_LINEAR) ? kMetricCkaLinear : kMetricFrobenius);
+  double* dist = reinterpret_cast<double*>(ws + l.dist);
   for (int b = 0; b < num_batches; ++b) {
     f.hidden = static_cast<const char*>(calib) + static_cast<size_t>(b) * n * cfg->hidden * eb;
     launch_gateup_down(cfg->dtype, cfg->inter, cfg->hidden, M, l.ksplit, f, s);
-    if (cosine)
+    if (metric == kMetricCosine) {
       hipLaunchKernelGGL(pair_cosine_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, M,
-                         reinterpret_cast<double*>(ws + l.dist));
-    else
+                         dist);
+    } else if (metric == kMetricCkaLinear) {
+      double* gram = reinterpret_cast<double*>(ws + l.gram);
+      double* rowsum = reinterpret_cast<double*>(ws + l.rowsum);
+      hipLaunchKernelGGL(gram_kernel, dim3(n, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, gram,
+                         rowsum);
+      hipLaunchKernelGGL(pair_hsic_kernel, dim3(M, M), dim3(256), 0, s, gram, rowsum, n, M, dist);
+    } else {
       hipLaunchKernelGGL(pair_distance_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden,
-                         M, reinterpret_cast<double*>(ws + l.dist));
-    hipLaunchKernelGGL(similarity_accumulate_kernel, dim3(1), dim3(1024), 0, s,
-                       reinterpret_cast<const double*>(ws + l.dist), M, b, num_batches, cosine,
+                         M, dist);
+    }
+    hipLaunchKernelGGL(similarity_accumulate_kernel, dim3(1), dim3(1024), 0, s, dist, M, b, num_batches, metric,
                        reinterpret_cast<double*>(ws + l.acc), sim);
   }
   return hip_status();

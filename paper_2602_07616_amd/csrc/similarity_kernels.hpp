@@ -4,8 +4,9 @@
 // decode path uses (a work list in which each expert owns all tokens of the
 // batch); then, with the Frobenius metric, x_pq = ||A_p - A_q||_F for all
 // pairs and Sim = 1 - x / max(x) per batch, or, with the cosine metric, the
-// mean over tokens of the cosine between the two experts' outputs; Sim is
-// accumulated over batches and averaged.
+// mean over tokens of the cosine between the two experts' outputs, or linear
+// CKA of the experts' Gram matrices; Sim is accumulated over batches and
+// averaged.
 #pragma once
 
 #include "common.hpp"
@@ -99,10 +100,92 @@ __global__ __launch_bounds__(256) void pair_cosine_kernel(const float* __restric
   if (threadIdx.x == 0) out[static_cast<size_t>(p) * M + q] = ((part[0] + part[1]) + (part[2] + part[3])) / n;
 }
 
+// Linear CKA (appendix "Centered Kernel Alignment"), step 1: the Gram matrix of every expert's
+// outputs with its diagonal set to zero, gram[e][i][j] = <A_e[i], A_e[j]> (i != j), and its row
+// sums.  Entries (i, j) and (j, i) are formed by the same operations in the same order, so the
+// matrix is symmetric to the bit.  grid (n, M), 256 threads: wavefront w takes j = w, w+4, ...;
+// fp64 accumulation.
+__global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ y, int ksplit, int rows, int n, int dh,
+                                                   double* __restrict__ gram, double* __restrict__ rowsum) {
+  __shared__ double part[4];
+  const int i = blockIdx.x, e = blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const size_t slice = static_cast<size_t>(rows) * dh;
+  const float* ai = y + (static_cast<size_t>(e) * n + i) * dh;
+  double row = 0.0;
+  for (int j = wave; j < n; j += 4) {
+    const float* aj = y + (static_cast<size_t>(e) * n + j) * dh;
+    double dot = 0.0;
+    for (int c = lane * 4; c < dh; c += 256) {
+      float4 a = *reinterpret_cast<const float4*>(ai + c), b = *reinterpret_cast<const float4*>(aj + c);
+      for (int s = 1; s < ksplit; ++s) {
+        const float4 a2 = *reinterpret_cast<const float4*>(ai + s * slice + c);
+        const float4 b2 = *reinterpret_cast<const float4*>(aj + s * slice + c);
+        a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+        b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
+      }
+      const double ax = a.x, ay = a.y, az = a.z, aw = a.w, bx = b.x, by = b.y, bz = b.z, bw = b.w;
+      dot += (ax * bx + ay * by) + (az * bz + aw * bw);
+    }
+    dot = wave_sum(dot);
+    if (j == i) dot = 0.0;
+    if (lane == 0) gram[(static_cast<size_t>(e) * n + i) * n + j] = dot;
+    row += dot;
+  }
+  if (lane == 0) part[wave] = row;
+  __syncthreads();
+  if (threadIdx.x == 0) rowsum[static_cast<size_t>(e) * n + i] = (part[0] + part[1]) + (part[2] + part[3]);
+}
+
+// Linear CKA, step 2: the unbiased estimator of HSIC for every pair of experts (Song et al. 2012,
+// the O(n^2) estimator the appendix refers to), from the zero-diagonal Gram matrices Kt_p, Kt_q:
+//   hsic[p][q] = [ tr(Kt_p Kt_q) + (1'Kt_p 1)(1'Kt_q 1) / ((n-1)(n-2)) - 2 (1'Kt_p Kt_q 1) / (n-2) ] / (n (n-3))
+// with tr(Kt_p Kt_q) = sum_ij Kt_p[i][j] Kt_q[i][j] (symmetric matrices) and 1'Kt_p Kt_q 1 = the
+// dot product of the two row-sum vectors.  grid (M, M), 256 threads; n >= 4.
+__global__ __launch_bounds__(256) void pair_hsic_kernel(const double* __restrict__ gram,
+                                                        const double* __restrict__ rowsum, int n, int M,
+                                                        double* __restrict__ hsic) {
+  __shared__ double part[4][4];
+  const int p = blockIdx.y, q = blockIdx.x;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const double* kp = gram + static_cast<size_t>(p) * n * n;
+  const double* kq = gram + static_cast<size_t>(q) * n * n;
+  double tr = 0.0, cross = 0.0, sp = 0.0, sq = 0.0;
+  for (int i = threadIdx.x; i < n * n; i += 256) tr += kp[i] * kq[i];
+  for (int i = threadIdx.x; i < n; i += 256) {
+    const double rp = rowsum[static_cast<size_t>(p) * n + i], rq = rowsum[static_cast<size_t>(q) * n + i];
+    cross += rp * rq;
+    sp += rp;
+    sq += rq;
+  }
+  tr = wave_sum(tr);
+  cross = wave_sum(cross);
+  sp = wave_sum(sp);
+  sq = wave_sum(sq);
+  if (lane == 0) {
+    part[0][wave] = tr;
+    part[1][wave] = cross;
+    part[2][wave] = sp;
+    part[3][wave] = sq;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double v[4];
+    for (int k = 0; k < 4; ++k) v[k] = (part[k][0] + part[k][1]) + (part[k][2] + part[k][3]);
+    const double dn = n;
+    hsic[static_cast<size_t>(p) * M + q] =
+        (v[0] + v[2] * v[3] / ((dn - 1.0) * (dn - 2.0)) - 2.0 * v[1] / (dn - 2.0)) / (dn * (dn - 3.0));
+  }
+}
+
+constexpr int kMetricFrobenius = 0, kMetricCosine = 1, kMetricCkaLinear = 2;
+
 // Frobenius: acc[p][q] (+)= 1 - dist/max(dist); cosine: acc[p][q] (+)= dist[p][q] (the pair
-// kernel's value as it is); on the last batch sim = acc / N.  One block of 1024 threads.
+// kernel's value as it is); linear CKA: acc[p][q] (+)= dist[p][q] / sqrt(dist[p][p] dist[q][q]),
+// dist holding the HSIC estimates (0 where a self-term is not positive: the quotient is undefined
+// there).  On the last batch sim = acc / N.  One block of 1024 threads.
 __global__ __launch_bounds__(1024) void similarity_accumulate_kernel(const double* __restrict__ dist, int M,
-                                                                     int batch, int num_batches, int cosine,
+                                                                     int batch, int num_batches, int metric,
                                                                      double* __restrict__ acc,
                                                                      float* __restrict__ sim) {
   __shared__ double smax[16];
@@ -116,7 +199,15 @@ __global__ __launch_bounds__(1024) void similarity_accumulate_kernel(const doubl
   double mx = 0.0;
   for (int w = 0; w < 16; ++w) mx = fmax(mx, smax[w]);
   for (int i = threadIdx.x; i < total; i += 1024) {
-    const double sv = cosine ? dist[i] : (mx > 0.0 ? 1.0 - dist[i] / mx : 1.0);  // all pairs identical: Sim = 1
+    double sv;
+    if (metric == kMetricCosine) {
+      sv = dist[i];
+    } else if (metric == kMetricCkaLinear) {
+      const double hp = dist[static_cast<size_t>(i / M) * M + i / M], hq = dist[static_cast<size_t>(i % M) * M + i % M];
+      sv = (hp > 0.0 && hq > 0.0) ? dist[i] / sqrt(hp * hq) : 0.0;
+    } else {
+      sv = mx > 0.0 ? 1.0 - dist[i] / mx : 1.0;  // all pairs identical: Sim = 1
+    }
     const double a = (batch == 0 ? 0.0 : acc[i]) + sv;
     acc[i] = a;
     if (batch == num_batches - 1) sim[i] = static_cast<float>(a / num_batches);

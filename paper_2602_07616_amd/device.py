@@ -38,12 +38,13 @@ def similarity_on_device(wl: Workload, weights=None, device="cuda", metric="frob
     """Expert-similarity matrix of the workload's layer from its calibration
     tokens, computed by the library (sere_similarity); returns a device fp32 [M, M]
     tensor.  `weights` = (router_w, w_gate_up, w_down, ...) already on the device.
-    metric: "frobenius" | "cosine"."""
+    metric: "frobenius" | "cosine" | "cka_linear"."""
     import torch
     sp = wl.spec
     n_batches, n_tokens = wl.calib.shape[0], wl.calib.shape[1]
     cfg = B.make_config(n_tokens, sp.hidden, sp.experts, min(sp.top_k, sp.experts), sp.inter, 0,
-                        sp.dtype, 1, 0.0, {"frobenius": 0, "cosine": B.SERE_FLAG_SIM_COSINE}[metric])
+                        sp.dtype, 1, 0.0, {"frobenius": 0, "cosine": B.SERE_FLAG_SIM_COSINE,
+                                          "cka_linear": B.SERE_FLAG_SIM_CKA_LINEAR}[metric])
     gu = to_device(wl.w_gate_up, sp.dtype, device) if weights is None else weights[1]
     dn = to_device(wl.w_down, sp.dtype, device) if weights is None else weights[2]
     calib = to_device(wl.calib, sp.dtype, device)

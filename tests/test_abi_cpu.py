@@ -53,7 +53,8 @@ BAD_CONFIGS = [
     ("num_shared", 17, B.SERE_ERR_BAD_SHAPE), ("top_k", 0, B.SERE_ERR_BAD_TOPK),
     ("top_k", 129, B.SERE_ERR_BAD_TOPK), ("select_top_k", 0, B.SERE_ERR_BAD_TOPK),
     ("select_top_k", 9, B.SERE_ERR_BAD_TOPK), ("dtype", 2, B.SERE_ERR_BAD_DTYPE),
-    ("flags", 4, B.SERE_ERR_BAD_FLAGS), ("flags", -1, B.SERE_ERR_BAD_FLAGS), ("threshold", float("nan"), B.SERE_ERR_NONFINITE_THRESHOLD),
+    ("flags", 8, B.SERE_ERR_BAD_FLAGS), ("flags", -1, B.SERE_ERR_BAD_FLAGS),
+    ("flags", B.SERE_FLAG_SIM_COSINE | B.SERE_FLAG_SIM_CKA_LINEAR, B.SERE_ERR_BAD_FLAGS), ("threshold", float("nan"), B.SERE_ERR_NONFINITE_THRESHOLD),
     ("threshold", float("inf"), B.SERE_ERR_NONFINITE_THRESHOLD),
 ]
 FAKE = 0x10000  # aligned, non-NULL, never dereferenced: validation fails first
@@ -126,3 +127,18 @@ def test_binding_raises_on_error():
     with pytest.raises(B.SereError) as e:
         B._check(B.load().sere_route(ctypes.byref(cfg), FAKE, FAKE, FAKE, None, FAKE, 0, None))
     assert e.value.status == B.SERE_ERR_BAD_TOPK
+
+
+def test_cka_similarity_batch_size_limits():
+    """Linear CKA needs 4 .. 512 tokens per calibration batch; checked before anything is enqueued."""
+    lib = B.load()
+    cfg = good()
+    cfg.flags = B.SERE_FLAG_SIM_CKA_LINEAR
+    for n in (3, 513):
+        assert B.sere_similarity_workspace_bytes(cfg, n) == 0
+        assert lib.sere_similarity(ctypes.byref(cfg), FAKE, 1, n, FAKE, FAKE, FAKE, FAKE, 1 << 40,
+                                   None) == B.SERE_ERR_BAD_SHAPE
+    plain = good()
+    assert B.sere_similarity_workspace_bytes(cfg, 64) > B.sere_similarity_workspace_bytes(plain, 64) > 0
+    assert lib.sere_similarity(ctypes.byref(cfg), FAKE, 1, 64, FAKE, FAKE, FAKE, FAKE, 0,
+                               None) == B.SERE_ERR_WORKSPACE_TOO_SMALL

@@ -450,13 +450,34 @@ def test_similarity_cosine_parity(dev, name):
         assert min(twins) > 0.9 and np.abs(got - np.eye(sp.experts)).max() > 0.9
 
 
+@pytest.mark.parametrize("name", ["tiny", "qwen3_b32"])
+def test_similarity_cka_linear_parity(dev, name):
+    """Linear CKA of sere_similarity against the oracle's.  Independent random experts score near 0
+    (the estimator is unbiased: also slightly below), twins near 1."""
+    wl, layer, _ = device_layer(dev, name)
+    print(f"cka similarity {name}", flush=True)
+    got = dev.similarity_on_device(wl, layer.weights(), metric="cka_linear").cpu().numpy()
+    want = oracle.similarity_cka_linear(wl.calib, wl.w_gate_up, wl.w_down, wl.spec.dtype)
+    tol = 1e-5 if wl.spec.dtype == wk.F32 else 5e-3
+    err = np.abs(got - want).max()
+    print(f"  max |cka - oracle| = {err:.3e}, range [{want.min():.3f}, {want.max():.3f}]", flush=True)
+    assert err <= tol, err
+    assert np.array_equal(got, got.T)
+    assert np.allclose(np.diag(got), 1.0, atol=1e-6)
+    sp = wl.spec
+    if sp.twin_n:
+        twins = [got[sp.twin_src + i, sp.twin_dst + i] for i in range(sp.twin_n)]
+        assert min(twins) > 0.9
+
+
 def test_similarity_with_long_calibration_batches(dev):
     """100 calibration tokens per batch: every expert is a work item of 100 rows, served in passes of
     up to 128 (gate/up) and 64 (down) token rows."""
     spec = wk.custom_spec("cal100", wk.BF16, 256, 12, 2, 192, 0, 4, 6100, twin_src=0, twin_dst=6, twin_n=6,
                           calib_batches=2, calib_tokens=100)
     wl = wk.make_workload(spec)
-    for metric, ref in (("frobenius", oracle.similarity_frobenius), ("cosine", oracle.similarity_cosine)):
+    for metric, ref in (("frobenius", oracle.similarity_frobenius), ("cosine", oracle.similarity_cosine),
+                        ("cka_linear", oracle.similarity_cka_linear)):
         got = dev.similarity_on_device(wl, metric=metric).cpu().numpy()
         want = ref(wl.calib, wl.w_gate_up, wl.w_down, spec.dtype)
         assert np.abs(got - want).max() <= 5e-3, (metric, np.abs(got - want).max())
