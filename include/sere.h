@@ -72,6 +72,7 @@ extern "C" {
 #define SERE_MAX_EXPERTS 256
 #define SERE_MAX_SHARED 16
 #define SERE_MAX_TOKENS 65536
+#define SERE_MAX_ROWS 1048576 /* T * (K + num_shared): rows of the expert-sorted slot list */
 
 /*
  * Problem description.  Names follow the paper: T tokens in the decode batch,
@@ -83,11 +84,11 @@ extern "C" {
  * hyper-parameters).
  */
 typedef struct sere_config {
-  int32_t num_tokens;   /* T, 1 .. SERE_MAX_TOKENS                                   */
-  int32_t hidden;       /* d_h, positive multiple of 64                              */
+  int32_t num_tokens;   /* T, 1 .. SERE_MAX_TOKENS; T * (K + num_shared) <= SERE_MAX_ROWS */
+  int32_t hidden;       /* d_h, positive multiple of 64, at most 65536              */
   int32_t num_experts;  /* M routed experts, 1 .. SERE_MAX_EXPERTS                   */
   int32_t top_k;        /* K, 1 .. M                                                 */
-  int32_t inter;        /* d_m, positive multiple of 64                              */
+  int32_t inter;        /* d_m, positive multiple of 64, at most 262144             */
   int32_t num_shared;   /* always-on shared experts, 0 .. SERE_MAX_SHARED; they see
                            every token with weight 1 and take no part in routing    */
   int32_t dtype;        /* SERE_F32 | SERE_BF16                                      */

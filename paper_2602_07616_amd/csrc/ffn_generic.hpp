@@ -142,11 +142,12 @@ struct CombineArgs {
 
 // out[t, r] = sum_k W[t,k] * y[pos(t,k), r] + sum_s y[A + s*T + t, r] (+ residual[t, r]); slots
 // in ascending k, then shared experts, then the residual; fp32, one rounding to the output dtype.
-// grid (ceil(dh/256), T), 256 threads.
+// grid ceil(dh/256) * T (a token's column blocks are neighbours), 256 threads.
 template <int DT>
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs p) {
-  const int r = blockIdx.x * 256 + threadIdx.x;
-  const int t = blockIdx.y;
+  const int col_blocks = (p.dh + 255) / 256;
+  const int r = static_cast<int>(blockIdx.x % col_blocks) * 256 + threadIdx.x;
+  const int t = blockIdx.x / col_blocks;
   if (r >= p.dh) return;
   const size_t slice = static_cast<size_t>(p.rows) * p.dh;
   float acc = 0.0f;

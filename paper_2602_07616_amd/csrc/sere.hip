@@ -86,9 +86,10 @@ static int check_config(const sere_config* c) {
   if (c->top_k < 1 || c->top_k > c->num_experts) return SERE_ERR_BAD_TOPK;
   if (c->select_top_k < 1 || c->select_top_k > c->top_k) return SERE_ERR_BAD_TOPK;
   if (!std::isfinite(c->threshold)) return SERE_ERR_NONFINITE_THRESHOLD;
-  // the sorted slot list is indexed with int32
+  // one work item per 32 rows of the sorted slot list at most, and the FFN grids carry the items in
+  // their y dimension (at most 65535)
   const int64_t rows = static_cast<int64_t>(c->num_tokens) * (c->top_k + c->num_shared);
-  if (rows > (1 << 24)) return SERE_ERR_BAD_SHAPE;
+  if (rows > SERE_MAX_ROWS) return SERE_ERR_BAD_SHAPE;
   return SERE_OK;
 }
 
@@ -292,7 +293,7 @@ static void launch_combine(const sere_config& c, const Layout& l, const Pointers
                            hipStream_t s) {
   CombineArgs ca{p.y, p.topk_w, p.route.slot_pos, (c.flags & SERE_FLAG_RESIDUAL) ? hidden : nullptr, out,
                  c.num_tokens, c.hidden, c.top_k, c.num_shared, l.ksplit, l.rows};
-  const dim3 grid((c.hidden + 255) / 256, c.num_tokens);
+  const dim3 grid(static_cast<unsigned>((c.hidden + 255) / 256) * c.num_tokens);
   if (c.dtype == SERE_F32)
     launch_stage(SERE_STAGE_COMBINE, s, combine_kernel<SERE_F32>, grid, dim3(256), ca);
   else

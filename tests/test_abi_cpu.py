@@ -142,3 +142,15 @@ def test_cka_similarity_batch_size_limits():
     assert B.sere_similarity_workspace_bytes(cfg, 64) > B.sere_similarity_workspace_bytes(plain, 64) > 0
     assert lib.sere_similarity(ctypes.byref(cfg), FAKE, 1, 64, FAKE, FAKE, FAKE, FAKE, 0,
                                None) == B.SERE_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_row_limit():
+    """T * (K + num_shared) is bounded (the FFN grids carry one work item per 32 rows in a grid dimension)."""
+    cfg = good()
+    cfg.num_tokens, cfg.top_k, cfg.select_top_k = 65536, 16, 1
+    assert B.sere_workspace_bytes(cfg) > 0
+    cfg.top_k = 17
+    assert B.sere_workspace_bytes(cfg) == 0
+    assert call_all(cfg) == [B.SERE_ERR_BAD_SHAPE] * 4
+    cfg.top_k, cfg.num_shared = 16, 1
+    assert call_all(cfg) == [B.SERE_ERR_BAD_SHAPE] * 4

@@ -239,6 +239,27 @@ def test_non_power_of_two_layer_at_full_size(dev):
         check_output(layer.out_to_host_f64()[tokens], want, spec.dtype, f"odd shape S={S}")
 
 
+@pytest.mark.parametrize("dtype", [wk.F32, wk.BF16])
+def test_maximum_token_count(dev, dtype):
+    """T = SERE_MAX_TOKENS (65536) on a small layer: the largest batch the library accepts.
+    Integers for the whole batch, outputs on sampled tokens, with and without re-routing."""
+    T = 65536
+    spec = wk.custom_spec("maxT", dtype, 128, 8, 2, 64, 1, T, 6200 + dtype, clusters=4, twin_src=0, twin_dst=4,
+                          twin_n=4, calib_batches=1, calib_tokens=8)
+    wl = wk.make_workload(spec)
+    sim = pins.rand_sim(6200, spec.experts)
+    layer = dev.DeviceLayer.from_workload(wl, sim, 1, 0.0)
+    tokens = list(range(11, T, 4099)) + [T - 1]
+    for S, rho in ((1, 0.0), (1, 0.6), (2, 0.0)):
+        print(f"max tokens dtype={dtype} S={S} rho={rho}", flush=True)
+        layer.set_knobs(S, rho)
+        layer.run_decode()
+        ref = oracle.route(wl.hidden, wl.router_w, spec.dtype, spec.top_k, sim, S, rho)
+        check_routing(layer.routing_to_host(), ref, layer.cfg)
+        want = oracle_output(wl, ref.rerouted_ids, ref.topk_weights, f"maxT{dtype}", tokens)
+        check_output(layer.out_to_host_f64()[tokens], want, spec.dtype, f"max tokens S={S}")
+
+
 # ------------------------------------------------------------ edge cases ---
 def small_case(dev, dtype, T, dh, M, K, dm, n_sh, seed, S, rho, sim=None, mutate=None):
     spec = wk.custom_spec(f"edge{seed}", dtype, dh, M, K, dm, n_sh, T, seed, weight_std=0.02,
