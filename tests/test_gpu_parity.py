@@ -286,6 +286,8 @@ EDGE = [
     (wk.BF16, 11, 128, 48, 12, 64, 0, 5, 0.3),     # K above twice the lanes per token (long-list merge)
     (wk.BF16, 6, 64, 256, 40, 64, 1, 7, 0.0),      # maximum expert count with a large K
     (wk.F32, 4, 64, 40, 40, 64, 0, 39, 0.0),       # K == M == 40, S = K - 1
+    (wk.BF16, 3, 64, 256, 256, 64, 0, 200, 0.0),   # K == M == 256: the largest top-K
+    (wk.F32, 5, 64, 4, 2, 64, 16, 1, 0.0),         # maximum number of shared experts
 ]
 
 
