@@ -405,6 +405,38 @@ def test_reroute_entry_point(dev):
         assert (bufs.topk_ids.cpu().numpy() == -1).all()      # not written by this entry point
 
 
+def test_reroute_entry_point_random_shapes(dev):
+    """sere_reroute on 96 seeded random shapes: any expert count up to 256, K up to 40, up to 3000
+    tokens (the regrouping pass then takes several rounds), every S, thresholds on and off."""
+    import torch
+    from paper_2602_07616_amd import binding as B
+    rng = np.random.default_rng(777)
+    for c in range(96):
+        M = int(rng.integers(1, 257))
+        K = int(rng.integers(1, min(M, 40) + 1))
+        T = int(rng.choice([1, 2, 5, 31, 33, 100, 257, 1000, 3000]))
+        S = int(rng.integers(1, K + 1))
+        levels = int(rng.choice([0, 0, 3, 8]))
+        sim = pins.rand_sim(8000 + c, M, levels=levels, symmetric=bool(c % 2))
+        rho = float(rng.choice([0.0, 0.3, 0.5, 0.9, -0.5, 2.0]))
+        ids = pins.rand_ids(9000 + c, T, K, M)
+        print(f"random reroute case {c}: T={T} K={K} M={M} S={S} rho={rho} levels={levels}", flush=True)
+        cfg = B.make_config(T, 64, M, K, 64, 0, B.SERE_BF16, S, rho)
+        bufs = B.RouteBuffers.allocate(cfg)
+        ws = B.alloc_workspace(cfg)
+        B.sere_reroute(cfg, torch.from_numpy(ids).cuda(), torch.from_numpy(sim).cuda(), bufs, ws)
+        torch.cuda.synchronize()
+        want, final, _, _ = oracle.reroute_sets(ids, sim, S, rho)
+        cnt, offs, tok, slot, n_after = oracle.compact(want, M)
+        assert np.array_equal(bufs.rerouted_ids.cpu().numpy(), want)
+        assert np.array_equal(bufs.count_after.cpu().numpy(), cnt)
+        assert np.array_equal(bufs.expert_offsets.cpu().numpy(), offs)
+        assert np.array_equal(bufs.sorted_token.cpu().numpy(), tok)
+        assert np.array_equal(bufs.sorted_slot.cpu().numpy(), slot)
+        assert np.array_equal(bufs.primary_mask.cpu().numpy(), oracle.primary_mask(ids, S, M))
+        assert bufs.num_active.cpu().numpy()[1] == n_after
+
+
 def test_two_runs_are_bit_identical(dev):
     wl, layer, sim = device_layer(dev, "qwen3_b32")
     layer.set_knobs(1, 0.0)
