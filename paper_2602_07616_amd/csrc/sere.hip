@@ -234,17 +234,21 @@ constexpr int kRouterTokensPerBlock = 4;  // batches of >= 256 tokens: a router 
 static int launch_router(const sere_config& c, const Pointers& p, const void* hidden,
                          const void* router_w, hipStream_t s) {
   const int lists = (c.num_experts + 15) / 16;
-  if (c.num_tokens >= 256) {
-    const dim3 grid(lists, (c.num_tokens + kRouterTokensPerBlock - 1) / kRouterTokensPerBlock);
-    if (c.dtype == SERE_F32)
-      launch_stage(SERE_STAGE_ROUTER, s, router_logits_tokens_kernel<SERE_F32, kRouterTokensPerBlock>, grid, dim3(256),
-                   hidden, router_w, p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
-    else
-      launch_stage(SERE_STAGE_ROUTER, s, router_logits_tokens_kernel<SERE_BF16, kRouterTokensPerBlock>, grid,
-                   dim3(256), hidden, router_w, p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden,
-                   p.ticket);
-    return hip_status();
-  }
+#define SERE_LAUNCH_ROUTER_TOKENS(TB)                                                                            \
+  do {                                                                                                          \
+    const dim3 grid(lists, (c.num_tokens + TB - 1) / TB);                                                       \
+    if (c.dtype == SERE_F32)                                                                                    \
+      launch_stage(SERE_STAGE_ROUTER, s, router_logits_tokens_kernel<SERE_F32, TB>, grid, dim3(256), hidden,    \
+                   router_w, p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);           \
+    else                                                                                                        \
+      launch_stage(SERE_STAGE_ROUTER, s, router_logits_tokens_kernel<SERE_BF16, TB>, grid, dim3(256), hidden,   \
+                   router_w, p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);           \
+    return hip_status();                                                                                        \
+  } while (0)
+  if (c.num_tokens >= 256) SERE_LAUNCH_ROUTER_TOKENS(kRouterTokensPerBlock);
+  // fewer tokens: two per fetch, if that still leaves a workgroup for every compute unit
+  if (c.num_tokens >= 64 && lists * ((c.num_tokens + 1) / 2) >= 256) SERE_LAUNCH_ROUTER_TOKENS(2);
+#undef SERE_LAUNCH_ROUTER_TOKENS
   const dim3 grid(lists, c.num_tokens);
   if (c.dtype == SERE_F32)
     launch_stage(SERE_STAGE_ROUTER, s, router_logits_kernel<SERE_F32>, grid, dim3(256), hidden, router_w, p.list_key,
