@@ -187,7 +187,7 @@ def cpu_baseline(wl, sim, S, rho, budget_s):
     t0 = time.perf_counter()
     step()
     first = time.perf_counter() - t0
-    reps = max(1, min(50, int(budget_s / max(first, 1e-3)) - 1))
+    reps = max(1, min(300, int(budget_s / max(first, 1e-3)) - 1))
     times = [first]
     for _ in range(reps):
         t0 = time.perf_counter()
