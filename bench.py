@@ -35,6 +35,8 @@ MEASURED_TRAFFIC = {
     ("qwen3_b32", 2, 0.0): {"gate_up": 204335652, "down": 106599894},
     ("qwen3_b128", 2, 0.0): {"gate_up": 660773920, "down": 350131729},
     ("mixtral_b64", 2, 0.0): {"gate_up": 1890675817, "down": 1060992118},
+    ("dsv2lite_b64", 2, 0.0): {"gate_up": 579056750, "down": 311375824},
+    ("qwen15_b32", 2, 0.0): {"gate_up": 359498547, "down": 189210759},
 }
 
 
