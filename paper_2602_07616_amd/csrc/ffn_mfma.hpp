@@ -437,9 +437,14 @@ __global__ __launch_bounds__(256, 4) void ffn_down_mfma(FfnArgs p) {
   const int kbeg = min(slice * per, blocks) << 6, kend = min((slice + 1) * per, blocks) << 6;
   if (fine) {
     const int r0 = (slab * kWavesPerBlock + wave) * kDownRows;
+    // a slice of d_m that ends half way through a 256-wide chunk (d_m = 1408: 5.5 chunks) is
+    // streamed in 128-wide chunks instead: the partial chunk's loads cost as much as a full one's
+    const bool half_tail = ((kend - kbeg) & 255) == 128;
     if (cnt <= kTile) {
       if (p.split_h) {
         down_group<1, 1, 256, true>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
+      } else if (half_tail) {
+        down_group<1, 1, 128, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
       } else {
         down_group<1, 1, 256, false>(p, W, r0, kbeg, kend, slice, off, cnt, lds);
       }
@@ -447,6 +452,8 @@ __global__ __launch_bounds__(256, 4) void ffn_down_mfma(FfnArgs p) {
       for (int q = 0; q < cnt; q += 2 * kTile) {
         if (p.split_h) {
           down_group<1, 2, 64, true>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
+        } else if (half_tail) {
+          down_group<1, 2, 128, false>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
         } else {
           down_group<1, 2, 256, false>(p, W, r0, kbeg, kend, slice, off + q, min(2 * kTile, cnt - q), lds);
         }
