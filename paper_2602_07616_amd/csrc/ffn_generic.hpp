@@ -151,19 +151,33 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs p) {
   if (r >= p.dh) return;
   const size_t slice = static_cast<size_t>(p.rows) * p.dh;
   float acc = 0.0f;
-  for (int k = 0; k < p.K; ++k) {
-    const int pos = p.slot_pos[t * p.K + k];
-    float v = 0.0f;
-    for (int s = 0; s < p.ksplit; ++s) v += p.y[s * slice + static_cast<size_t>(pos) * p.dh + r];
-    acc = fmaf(p.topk_w[t * p.K + k], v, acc);
-  }
+  // Contributions are added in ascending order, eight at a time: the eight positions, then the
+  // eight rows of y are requested together (one memory round trip each instead of one per
+  // contribution), then the eight fused multiply-adds run in order.
+  constexpr int kBatch = 8;
+  auto add = [&](int count, auto&& pos_of, auto&& weight_of) {
+    for (int k0 = 0; k0 < count; k0 += kBatch) {
+      int pos[kBatch];
+      float w[kBatch], v[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int k = min(k0 + j, count - 1);
+        pos[j] = pos_of(k);
+        w[j] = weight_of(k);
+        v[j] = 0.0f;
+      }
+      for (int s = 0; s < p.ksplit; ++s) {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) v[j] += p.y[s * slice + static_cast<size_t>(pos[j]) * p.dh + r];
+      }
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j)
+        if (k0 + j < count) acc = fmaf(w[j], v[j], acc);
+    }
+  };
+  add(p.K, [&](int k) { return p.slot_pos[t * p.K + k]; }, [&](int k) { return p.topk_w[t * p.K + k]; });
   const int A = p.T * p.K;
-  for (int sh = 0; sh < p.n_sh; ++sh) {
-    const int pos = A + sh * p.T + t;
-    float v = 0.0f;
-    for (int s = 0; s < p.ksplit; ++s) v += p.y[s * slice + static_cast<size_t>(pos) * p.dh + r];
-    acc += v;
-  }
+  add(p.n_sh, [&](int sh) { return A + sh * p.T + t; }, [](int) { return 1.0f; });
   if (p.residual != nullptr) {
     if (DT == SERE_F32)
       acc += static_cast<const float*>(p.residual)[static_cast<size_t>(t) * p.dh + r];
