@@ -26,7 +26,8 @@
  *     device side effects.  No exception or abort crosses this boundary.
  *   - Not checked on the device (preconditions): hidden states, router
  *     weights and `sim` are finite; `topk_ids` handed to sere_reroute lie in
- *     [0, M).
+ *     [0, M) (an id outside that range is read as the nearest one inside it:
+ *     the result is then meaningless, but no access leaves its buffer).
  *   - Calls are re-entrant as long as concurrent calls use distinct
  *     workspaces and outputs.
  *   - Expert indices are 0-based.

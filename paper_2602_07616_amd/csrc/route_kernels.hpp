@@ -435,7 +435,11 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int M = p.M, K = p.K, S = p.S;
   const int A = p.T * K;
-  auto id_at = [&](int a) -> int { return IDS_IN_LDS ? static_cast<int>(s.ids8[a]) : p.topk_ids[a]; };
+  // ids read from memory may be a caller's (sere_reroute): clamped into [0, M) so that an id outside
+  // that range, a broken precondition, cannot send any access out of bounds
+  auto id_at = [&](int a) -> int {
+    return IDS_IN_LDS ? static_cast<int>(s.ids8[a]) : min(max(p.topk_ids[a], 0), M - 1);
+  };
 
   if (tid < SERE_MAX_EXPERTS) {
     s.cnt_b[tid] = 0;

@@ -405,6 +405,30 @@ def test_reroute_entry_point(dev):
         assert (bufs.topk_ids.cpu().numpy() == -1).all()      # not written by this entry point
 
 
+def test_reroute_clamps_out_of_range_ids(dev):
+    """Ids outside [0, M) break a precondition of sere_reroute; the kernel reads them as the
+    nearest valid id, so the call stays inside its buffers and equals the call on clamped ids."""
+    import torch
+    from paper_2602_07616_amd import binding as B
+    T, K, M, S, rho = 50, 4, 24, 2, 0.3
+    sim = pins.rand_sim(5300, M)
+    ids = pins.rand_ids(5301, T, K, M)
+    bad = ids.copy()
+    bad[3, 1], bad[7, 0], bad[20, 3], bad[49, 2] = -7, M, M + 1000, -(2 ** 31)
+    cfg = B.make_config(T, 64, M, K, 64, 0, B.SERE_BF16, S, rho)
+    bufs = B.RouteBuffers.allocate(cfg)
+    ws = B.alloc_workspace(cfg)
+    B.sere_reroute(cfg, torch.from_numpy(bad).cuda(), torch.from_numpy(sim).cuda(), bufs, ws)
+    torch.cuda.synchronize()
+    clamped = np.clip(bad, 0, M - 1).astype(np.int32)
+    want, _, _, _ = oracle.reroute_sets(clamped, sim, S, rho)
+    cnt, offs, tok, slot, n_after = oracle.compact(want, M)
+    assert np.array_equal(bufs.rerouted_ids.cpu().numpy(), want)
+    assert np.array_equal(bufs.count_after.cpu().numpy(), cnt)
+    assert np.array_equal(bufs.sorted_token.cpu().numpy(), tok)
+    assert np.array_equal(bufs.sorted_slot.cpu().numpy(), slot)
+
+
 def test_reroute_entry_point_random_shapes(dev):
     """sere_reroute on 96 seeded random shapes: any expert count up to 256, K up to 40, up to 3000
     tokens (the regrouping pass then takes several rounds), every S, thresholds on and off."""
