@@ -154,3 +154,23 @@ def test_row_limit():
     assert call_all(cfg) == [B.SERE_ERR_BAD_SHAPE] * 4
     cfg.top_k, cfg.num_shared = 16, 1
     assert call_all(cfg) == [B.SERE_ERR_BAD_SHAPE] * 4
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/sere.h compiles as C99 with warnings as errors, and a C program that takes the
+    address of every declared entry point links against the library (no call is made: no GPU)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    names = declared_functions()
+    src = tmp_path / "use_abi.c"
+    body = "\n".join(f"  table[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
+    src.write_text('#include "sere.h"\n#include <stdio.h>\nint main(void) {\n'
+                   f"  void (*table[{len(names)}])(void);\n{body}\n"
+                   f'  printf("%d\\n", (int)(sizeof(sere_config) + sizeof(sere_route_out)) + (table[0] != 0));\n'
+                   "  return 0;\n}\n")
+    lib_dir = os.path.dirname(B.LIB_PATH)
+    exe = tmp_path / "use_abi"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe), "-L", lib_dir, "-l:" + os.path.basename(B.LIB_PATH),
+                    "-Wl,-rpath," + lib_dir, "-Wl,--unresolved-symbols=ignore-in-shared-libs"], check=True)
+    assert exe.exists()
