@@ -1,4 +1,5 @@
-"""Compile the HIP library for gfx950 into paper_2602_07616_amd/libsere.so.
+"""Compile the HIP library for gfx950 into paper_2602_07616_amd/libsere.so, and the plain-C
+caller of its ABI (csrc/abi_cli.c) into paper_2602_07616_amd/abi_cli.
 
 hipcc cross-compiles without a GPU.  Packed-fp32 instruction selection is
 switched off for device code (see the flag below); the host pass prints a
@@ -13,6 +14,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsere.so")
+CLI = os.path.join(HERE, "abi_cli")
+ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 
 
 def sources():
@@ -45,7 +48,24 @@ def build(force: bool = True, verbose: bool = False) -> str:
         noise = "is not a recognized feature for this target"
         print("\n".join(ln for ln in r.stderr.splitlines() if noise not in ln))
     os.replace(tmp, LIB)
+    build_cli()
     return LIB
+
+
+def build_cli() -> str:
+    """The C program links against libsere.so (found next to it at run time) and the HIP runtime."""
+    tmp = f"{CLI}.{os.getpid()}.tmp"
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(ROCM, "include"), "-I", os.path.join(os.path.dirname(HERE), "include"),
+           os.path.join(CSRC, "abi_cli.c"), "-o", tmp,
+           "-L", HERE, "-l:libsere.so", "-L", os.path.join(ROCM, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(ROCM, "lib"),
+           "-Wl,--unresolved-symbols=ignore-in-shared-libs"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("gcc failed on abi_cli.c:\n" + r.stdout + r.stderr)
+    os.replace(tmp, CLI)
+    return CLI
 
 
 if __name__ == "__main__":
