@@ -36,8 +36,10 @@ static Layout make_layout(const sere_config& c) {
   Layout l{};
   const size_t T = c.num_tokens, M = c.num_experts, K = c.top_k, A = T * K;
   const size_t R = A + static_cast<size_t>(c.num_shared) * T;
-  // an expert's rows are cut into items of <= kItemRows: at most one partial item per expert
-  const size_t W = M + c.num_shared + R / kItemRows;
+  // an expert's rows are cut into items of <= kItemRows: at most one partial item per expert, and
+  // never more items than rows (small batches: far fewer than M)
+  const size_t routed_items = M + A / kItemRows < A ? M + A / kItemRows : A;
+  const size_t W = routed_items + c.num_shared * ((T + kItemRows - 1) / kItemRows);
   l.rows = static_cast<int>(R);
   l.ksplit = down_ksplit(c);
   l.max_work = static_cast<int>(W);
