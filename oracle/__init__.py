@@ -221,6 +221,26 @@ class OracleLib:
                                             dh, M, dm, _p(act), _p(gram), _p(sim))
         return sim
 
+    def similarity_cka(self, calib, w_gate_up, w_down, dtype: int, kernel: str, p0: float = 0.0,
+                       p1: float = 0.0) -> np.ndarray:
+        """-> S [M,M] float64, CKA with the kernel "linear", "rbf" (p0 = sigma) or "poly"
+        (p0 = c, p1 = degree) of the appendix on similarity metrics."""
+        calib = _check(calib, dtype)
+        w_gate_up, w_down = _check(w_gate_up, dtype), _check(w_down, dtype)
+        N, n, dh = calib.shape
+        M, dm2, _ = w_gate_up.shape
+        dm = dm2 // 2
+        assert n >= 4
+        kid = {"linear": 0, "rbf": 1, "poly": 2}[kernel]
+        assert kid != 1 or p0 > 0.0
+        assert kid != 2 or (p1 >= 1 and float(p1).is_integer())
+        act = np.empty((M, n, dh), dtype=np.float64)
+        gram = np.empty((M, n, n), dtype=np.float64)
+        sim = np.empty((M, M), dtype=np.float64)
+        self.c.oracle_similarity_cka(_p(calib), _p(w_gate_up), _p(w_down), dtype, N, n, dh, M, dm, kid,
+                                     ctypes.c_double(p0), ctypes.c_double(p1), _p(act), _p(gram), _p(sim))
+        return sim
+
     def route(self, hidden, router_w, dtype: int, K: int, sim, S: int,
               rho: float) -> LayerResult:
         """Routing half of the layer (no expert is executed)."""

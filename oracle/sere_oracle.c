@@ -507,9 +507,33 @@ static double hsic_unbiased(const double *Kt, const double *Lt, int n)
     return (tr + sk * sl / ((dn - 1.0) * (dn - 2.0)) - 2.0 * cross / (dn - 2.0)) / (dn * (dn - 3.0));
 }
 
-void oracle_similarity_cka_linear(const void *calib, const void *w_gate_up, const void *w_down,
-                                  int dtype, int N, int n, int dh, int M, int dm, double *act,
-                                  double *gram, double *sim)
+/*
+ * One entry of a Gram matrix for the three kernels of the appendix "Centered
+ * Kernel Alignment", x and y being two rows of an expert's outputs:
+ *   kernel 0, linear:      <x, y>
+ *   kernel 1, RBF:         exp(-||x - y||^2 / (2 sigma^2)),  sigma = p0
+ *   kernel 2, polynomial:  (<x, y> + c)^d,  c = p0, d = p1 (a positive integer)
+ */
+static double cka_kernel_value(const double *x, const double *y, int dh, int kernel, double p0,
+                               double p1)
+{
+    double dot = 0.0, dist2 = 0.0;
+    for (int k = 0; k < dh; ++k) {
+        dot += x[k] * y[k];
+        dist2 += (x[k] - y[k]) * (x[k] - y[k]);
+    }
+    if (kernel == 1)
+        return exp(-dist2 / (2.0 * p0 * p0));
+    if (kernel == 2)
+        return pow(dot + p0, p1);
+    return dot;
+}
+
+/* CKA with the kernel chosen by (kernel, p0, p1) as above; everything else as
+ * described before hsic_unbiased. */
+void oracle_similarity_cka(const void *calib, const void *w_gate_up, const void *w_down,
+                           int dtype, int N, int n, int dh, int M, int dm, int kernel, double p0,
+                           double p1, double *act, double *gram, double *sim)
 {
     size_t gu = (size_t)2 * dm * dh, dn = (size_t)dh * dm;
     double *self = (double *)malloc(sizeof(double) * (size_t)M);
@@ -534,9 +558,7 @@ void oracle_similarity_cka_linear(const void *calib, const void *w_gate_up, cons
                 for (int c = 0; c < n; ++c) {
                     const double *x = act + ((size_t)j * n + r) * dh;
                     const double *y = act + ((size_t)j * n + c) * dh;
-                    double dot = 0.0;
-                    for (int k = 0; k < dh; ++k)
-                        dot += x[k] * y[k];
+                    double dot = cka_kernel_value(x, y, dh, kernel, p0, p1);
                     gram[((size_t)j * n + r) * n + c] = (r == c) ? 0.0 : dot;
                 }
         for (int j = 0; j < M; ++j)
@@ -554,4 +576,13 @@ void oracle_similarity_cka_linear(const void *calib, const void *w_gate_up, cons
     for (size_t i = 0; i < (size_t)M * M; ++i)
         sim[i] = sim[i] * (1.0 / (double)N);
     free(self);
+}
+
+/* linear-kernel CKA */
+void oracle_similarity_cka_linear(const void *calib, const void *w_gate_up, const void *w_down,
+                                  int dtype, int N, int n, int dh, int M, int dm, double *act,
+                                  double *gram, double *sim)
+{
+    oracle_similarity_cka(calib, w_gate_up, w_down, dtype, N, n, dh, M, dm, 0, 0.0, 0.0, act, gram,
+                          sim);
 }

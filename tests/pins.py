@@ -571,8 +571,60 @@ def pin_similarity_cka(o):
     assert np.all(s[1] == 0.0) and np.all(s[:, 1] == 0.0) and abs(s[0, 0] - 1.0) < 1e-13
 
 
+def pin_similarity_cka_kernels(o):
+    """CKA with the RBF and the polynomial kernel: Gram matrices written with numpy, HSIC by brute
+    force over 4-tuples; invariance under orthogonal maps of the output space; a twin scores 1; the
+    polynomial kernel of degree 1 and offset 0 is the linear kernel."""
+    for dtype, seed in ((wk.F32, 131), (wk.BF16, 132)):
+        c = rng_case(seed, dtype, 1, 24, 4, 10)
+        c["w_gate_up"][3] = c["w_gate_up"][1]
+        c["w_down"][3] = c["w_down"][1]                       # exact twin of expert 1
+        cal = wk.to_storage(wk.std_normal(seed, "cal", 2 * 6 * 24), dtype).reshape(2, 6, 24)
+        N, M = cal.shape[0], c["w_gate_up"].shape[0]
+        acts = [[np_expert(f64(cal[b], dtype), f64(c["w_gate_up"][e], dtype), f64(c["w_down"][e], dtype))
+                 for e in range(M)] for b in range(N)]
+        sq = np.array([np.sum((a[:, None, :] - a[None, :, :]) ** 2, axis=2) for a in acts[0]])
+        sigma = float(np.sqrt(np.median(sq[sq > 0])))        # kernel values spread over (0, 1)
+        kernels = {
+            ("rbf", sigma, 0.0): lambda a: np.exp(-np.sum((a[:, None, :] - a[None, :, :]) ** 2, axis=2)
+                                                  / (2.0 * sigma ** 2)),
+            ("poly", 0.5, 3.0): lambda a: (a @ a.T + 0.5) ** 3,
+        }
+        for (kind, p0, p1), gram_of in kernels.items():
+            s = o.similarity_cka(cal, c["w_gate_up"], c["w_down"], dtype, kind, p0, p1)
+            want = np.zeros((M, M))
+            for b in range(N):
+                grams = [gram_of(a) for a in acts[b]]
+                h = np.array([[_hsic_ustatistic(grams[p], grams[q]) for q in range(M)] for p in range(M)])
+                want += h / np.sqrt(np.outer(np.diag(h), np.diag(h)))
+            want /= N
+            assert np.allclose(s, want, rtol=1e-8, atol=1e-10), (kind, np.abs(s - want).max())
+            assert np.allclose(s, s.T, rtol=0, atol=1e-13)
+            assert abs(s[1, 3] - 1.0) < 1e-12 and np.allclose(np.diag(s), 1.0, atol=1e-12)
+        lin = o.similarity_cka_linear(cal, c["w_gate_up"], c["w_down"], dtype)
+        assert np.allclose(o.similarity_cka(cal, c["w_gate_up"], c["w_down"], dtype, "poly", 0.0, 1.0), lin,
+                           rtol=0, atol=1e-13)
+        assert np.array_equal(o.similarity_cka(cal, c["w_gate_up"], c["w_down"], dtype, "linear"), lin)
+        rbf = o.similarity_cka(cal, c["w_gate_up"], c["w_down"], dtype, "rbf", sigma)
+        assert np.abs(rbf - lin).max() > 1e-3                # a different quantity from the linear kernel
+    # both kernels depend on the outputs through inner products and distances only: an orthogonal
+    # map of an expert's output space leaves its Gram matrix, hence every CKA value, unchanged
+    c = rng_case(133, wk.F32, 1, 16, 3, 6)
+    q_mat, _ = np.linalg.qr(wk.std_normal(133, "q", 16 * 16).reshape(16, 16))
+    cal = wk.std_normal(133, "cal", 2 * 7 * 16).reshape(2, 7, 16)
+    rot = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in c.items()}
+    rot["w_down"][2] = (q_mat @ c["w_down"][2].astype(np.float64)).astype(np.float32)
+    a0 = np_expert(cal[0].astype(np.float64), c["w_gate_up"][0].astype(np.float64), c["w_down"][0].astype(np.float64))
+    sq = np.sum((a0[:, None, :] - a0[None, :, :]) ** 2, axis=2)
+    sigma = float(np.sqrt(np.median(sq[sq > 0])))
+    for kind, p0, p1 in (("rbf", sigma, 0.0), ("poly", float(np.mean(np.sum(a0 * a0, axis=1))), 2.0)):
+        a = o.similarity_cka(cal, c["w_gate_up"], c["w_down"], wk.F32, kind, p0, p1)
+        b = o.similarity_cka(cal, rot["w_gate_up"], rot["w_down"], wk.F32, kind, p0, p1)
+        assert np.abs(a - b).max() < 1e-4, (kind, np.abs(a - b).max())   # rotated weights rounded to fp32
+
+
 ALL_PINS = [
-    pin_similarity_cka,
+    pin_similarity_cka, pin_similarity_cka_kernels,
     pin_similarity_cosine,
     pin_router_logits_library, pin_topk_order_and_gate, pin_fig2_behaviour,
     pin_reroute_hand_cases, pin_reroute_against_brute, pin_reroute_invariants, pin_compact,

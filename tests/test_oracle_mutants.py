@@ -64,6 +64,14 @@ MUTANTS = [
     ("cka_sum_term_weight", "sk * sl / ((dn - 1.0) * (dn - 2.0))", "sk * sl / (dn * dn)", [pins.pin_similarity_cka]),
     ("cka_sum_term_dropped", "tr + sk * sl / ((dn - 1.0) * (dn - 2.0))", "tr", [pins.pin_similarity_cka]),
     ("cka_no_sqrt", "sqrt(self[p] * self[q]);", "(self[p] * self[q]);", [pins.pin_similarity_cka]),
+    ("cka_rbf_bandwidth_not_squared", "return exp(-dist2 / (2.0 * p0 * p0));", "return exp(-dist2 / (2.0 * p0));",
+     [pins.pin_similarity_cka_kernels]),
+    ("cka_rbf_no_factor_two", "return exp(-dist2 / (2.0 * p0 * p0));", "return exp(-dist2 / (p0 * p0));",
+     [pins.pin_similarity_cka_kernels]),
+    ("cka_rbf_distance_not_squared", "dist2 += (x[k] - y[k]) * (x[k] - y[k]);", "dist2 += fabs(x[k] - y[k]);",
+     [pins.pin_similarity_cka_kernels]),
+    ("cka_poly_offset_dropped", "return pow(dot + p0, p1);", "return pow(dot, p1);", [pins.pin_similarity_cka_kernels]),
+    ("cka_poly_degree_ignored", "return pow(dot + p0, p1);", "return dot + p0;", [pins.pin_similarity_cka_kernels]),
     ("cka_not_averaged", "sim[i] = sim[i] * (1.0 / (double)N);", "sim[i] = sim[i];", [pins.pin_similarity_cka]),
 ]
 
