@@ -56,6 +56,8 @@ extern "C" {
                                              that exclude each other                     */
 #define SERE_ERR_NONFINITE_THRESHOLD (-8) /* threshold is NaN or infinite                */
 #define SERE_ERR_HIP (-9)                 /* a HIP launch reported an error              */
+#define SERE_ERR_BAD_KERNEL (-10)         /* sere_similarity_cka: unknown kernel or a
+                                             parameter outside its range                 */
 
 /* sere_config.flags */
 #define SERE_FLAG_RESIDUAL 1 /* sere_moe_decode[_baseline]: out = hidden + layer(hidden), the
@@ -211,7 +213,7 @@ int sere_moe_decode_baseline(const sere_config *cfg, const void *hidden, const v
  * [tr(Kt_p Kt_q) + (1'Kt_p 1)(1'Kt_q 1)/((n-1)(n-2)) - 2 (1'Kt_p Kt_q 1)/(n-2)]
  * / (n(n-3))); a pair with a non-positive self-term contributes 0; needs
  * 4 <= batch_tokens <= 512 (else SERE_ERR_BAD_SHAPE).  The RBF and polynomial
- * kernels of that appendix are not built (their parameters are not given).
+ * kernels of that appendix: sere_similarity_cka below.
  *   calib [num_batches, batch_tokens, d_h]  dtype, device
  *   sim   [M, M] fp32, device, written
  * Uses cfg->hidden, num_experts, inter, dtype (the other fields must be valid
@@ -225,6 +227,29 @@ size_t sere_similarity_workspace_bytes(const sere_config *cfg, int32_t batch_tok
 int sere_similarity(const sere_config *cfg, const void *calib, int32_t num_batches,
                     int32_t batch_tokens, const void *w_gate_up, const void *w_down, float *sim,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The same estimate with centered kernel alignment and any of the three
+ * kernels of the appendix "Centered Kernel Alignment" (cfg->flags' metric bits
+ * are ignored): K_p[i][j] = k(A_p[i], A_p[j]) over the batch's tokens with
+ *   SERE_CKA_LINEAR  k(x, y) = <x, y>                          (no parameter)
+ *   SERE_CKA_RBF     k(x, y) = exp(-|x - y|^2 / (2 sigma^2))   param0 = sigma > 0
+ *   SERE_CKA_POLY    k(x, y) = (<x, y> + c)^d                  param0 = c, param1 = d,
+ *                                                              an integer in 1 .. 16
+ * and Sim(p,q) = HSIC(K_p,K_q) / sqrt(HSIC(K_p,K_p) HSIC(K_q,K_q)) with the
+ * unbiased estimator described above.  The paper does not state the kernel
+ * parameters it used; they are the caller's.  4 <= batch_tokens <= 512.
+ * SERE_ERR_BAD_KERNEL for an unknown kernel or a parameter outside its range.
+ * Workspace: sere_similarity_cka_workspace_bytes(cfg, batch_tokens).
+ */
+#define SERE_CKA_LINEAR 0
+#define SERE_CKA_RBF 1
+#define SERE_CKA_POLY 2
+size_t sere_similarity_cka_workspace_bytes(const sere_config *cfg, int32_t batch_tokens);
+int sere_similarity_cka(const sere_config *cfg, const void *calib, int32_t num_batches,
+                        int32_t batch_tokens, const void *w_gate_up, const void *w_down,
+                        int32_t kernel, double param0, double param1, float *sim, void *workspace,
+                        size_t workspace_bytes, void *hip_stream);
 
 /*
  * Per-kernel timing for benchmarks.  While enabled, every kernel the calls

@@ -27,6 +27,8 @@ SERE_ERR_WORKSPACE_TOO_SMALL = -6
 SERE_ERR_BAD_FLAGS = -7
 SERE_ERR_NONFINITE_THRESHOLD = -8
 SERE_ERR_HIP = -9
+SERE_ERR_BAD_KERNEL = -10
+SERE_CKA_LINEAR, SERE_CKA_RBF, SERE_CKA_POLY = 0, 1, 2
 
 STAGES = ("router", "route", "gate_up", "down", "combine")
 
@@ -86,6 +88,11 @@ def load() -> ctypes.CDLL:
     lib.sere_similarity_workspace_bytes.argtypes = [cfgp, ctypes.c_int32]
     lib.sere_similarity.restype = ci
     lib.sere_similarity.argtypes = [cfgp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp, sz, vp]
+    lib.sere_similarity_cka_workspace_bytes.restype = sz
+    lib.sere_similarity_cka_workspace_bytes.argtypes = [cfgp, ctypes.c_int32]
+    lib.sere_similarity_cka.restype = ci
+    lib.sere_similarity_cka.argtypes = [cfgp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.c_int32,
+                                        ctypes.c_double, ctypes.c_double, vp, vp, sz, vp]
     lib.sere_stage_timing.restype = ci
     lib.sere_stage_timing.argtypes = [ci]
     lib.sere_stage_timing_read.restype = ci
@@ -215,6 +222,18 @@ def sere_similarity(cfg, calib, num_batches, batch_tokens, w_gate_up, w_down, si
     _check(load().sere_similarity(ctypes.byref(cfg), _ptr(calib), num_batches, batch_tokens,
                                   _ptr(w_gate_up), _ptr(w_down), _ptr(sim), _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def sere_similarity_cka_workspace_bytes(cfg: sere_config, batch_tokens: int) -> int:
+    return int(load().sere_similarity_cka_workspace_bytes(ctypes.byref(cfg), batch_tokens))
+
+
+def sere_similarity_cka(cfg, calib, num_batches, batch_tokens, w_gate_up, w_down, kernel, param0, param1, sim,
+                        workspace, stream=None) -> None:
+    _check(load().sere_similarity_cka(ctypes.byref(cfg), _ptr(calib), num_batches, batch_tokens,
+                                      _ptr(w_gate_up), _ptr(w_down), kernel, float(param0), float(param1),
+                                      _ptr(sim), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)))
 
 
 def sere_stage_timing(enable: bool) -> None:

@@ -409,7 +409,7 @@ static int decode(const sere_config* cfg, const void* hidden, const void* router
 
 // ------------------------------------------------------------- similarity ---
 struct SimLayout {
-  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, gram, rowsum, total;
+  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, gram, rowsum, diag, total;
   int rows, ksplit;
 };
 
@@ -436,6 +436,7 @@ static SimLayout make_sim_layout(const sere_config& c, int n) {
   if (c.flags & SERE_FLAG_SIM_CKA_LINEAR) {  // Gram matrix and its row sums per expert
     l.gram = take(R * n * sizeof(double));
     l.rowsum = take(R * sizeof(double));
+    l.diag = take(R * sizeof(double));
   }
   l.total = o;
   return l;
@@ -447,6 +448,85 @@ static int check_similarity_sizes(const sere_config& c, int32_t num_batches, int
   if (num_batches < 1 || num_batches > 4096 || n < 1 || n > 4096) return SERE_ERR_BAD_SHAPE;
   if ((c.flags & SERE_FLAG_SIM_CKA_LINEAR) && (n < kCkaMinTokens || n > kCkaMaxTokens)) return SERE_ERR_BAD_SHAPE;
   return SERE_OK;
+}
+
+static int similarity(const sere_config* cfg, const void* calib, int32_t num_batches, int32_t batch_tokens,
+                      const void* w_gate_up, const void* w_down, int cka_kernel, double p0, double p1, float* sim,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = check_config(cfg);
+  if (st != SERE_OK) return st;
+  st = check_similarity_sizes(*cfg, num_batches, batch_tokens);
+  if (st != SERE_OK) return st;
+  PtrCheck pc;
+  pc.need(calib);
+  pc.need(w_gate_up);
+  pc.need(w_down);
+  pc.need(sim);
+  if (pc.status != SERE_OK) return pc.status;
+  const SimLayout l = make_sim_layout(*cfg, batch_tokens);
+  if (workspace == nullptr) return SERE_ERR_NULL_PTR;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SERE_ERR_MISALIGNED;
+  if (workspace_bytes < l.total) return SERE_ERR_WORKSPACE_TOO_SMALL;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  const int M = cfg->num_experts, n = batch_tokens;
+  FfnArgs f{};
+  f.w_gate_up = w_gate_up;
+  f.w_down = w_down;
+  f.sorted_token = reinterpret_cast<int32_t*>(ws + l.sorted_token);
+  f.work_expert = reinterpret_cast<int32_t*>(ws + l.work_expert);
+  f.work_off = reinterpret_cast<int32_t*>(ws + l.work_off);
+  f.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
+  f.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
+  f.h = reinterpret_cast<float*>(ws + l.h);
+  f.y = reinterpret_cast<float*>(ws + l.y);
+  f.T = n;
+  f.dh = cfg->hidden;
+  f.dm = cfg->inter;
+  f.M = M;
+  f.K = 1;
+  f.n_sh = 0;
+  f.ksplit = l.ksplit;
+  f.rows = l.rows;
+  f.split_h = wants_split_h(*cfg);
+  hipLaunchKernelGGL(similarity_worklist_kernel, dim3((M * n + 255) / 256), dim3(256), 0, s, M, n,
+                     const_cast<int32_t*>(f.sorted_token), const_cast<int32_t*>(f.work_expert),
+                     const_cast<int32_t*>(f.work_off), const_cast<int32_t*>(f.work_cnt),
+                     const_cast<int32_t*>(f.n_work));
+  const size_t eb = cfg->dtype == SERE_F32 ? 4 : 2;
+  const int metric = (cfg->flags & SERE_FLAG_SIM_COSINE)
+                         ? kMetricCosine
+                         : ((cfg->flags & SERE_FLAG_SIM_CKA_LINEAR) ? kMetricCkaLinear : kMetricFrobenius);
+  double* dist = reinterpret_cast<double*>(ws + l.dist);
+  for (int b = 0; b < num_batches; ++b) {
+    f.hidden = static_cast<const char*>(calib) + static_cast<size_t>(b) * n * cfg->hidden * eb;
+    launch_gateup_down(cfg->dtype, cfg->inter, cfg->hidden, M, l.ksplit, f, s);
+    if (metric == kMetricCosine) {
+      hipLaunchKernelGGL(pair_cosine_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, M,
+                         dist);
+    } else if (metric == kMetricCkaLinear) {
+      double* gram = reinterpret_cast<double*>(ws + l.gram);
+      double* rowsum = reinterpret_cast<double*>(ws + l.rowsum);
+      if (cka_kernel == kCkaLinear) {
+        hipLaunchKernelGGL(gram_kernel, dim3(n, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, gram,
+                           rowsum, static_cast<double*>(nullptr));
+      } else {
+        double* diag = reinterpret_cast<double*>(ws + l.diag);
+        hipLaunchKernelGGL(gram_kernel, dim3(n, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, gram,
+                           static_cast<double*>(nullptr), diag);
+        hipLaunchKernelGGL(gram_transform_kernel, dim3(n, M), dim3(256), 0, s, gram, diag, n, cka_kernel, p0,
+                           static_cast<int>(p1), rowsum);
+      }
+      hipLaunchKernelGGL(pair_hsic_kernel, dim3(M, M), dim3(256), 0, s, gram, rowsum, n, M, dist);
+    } else {
+      hipLaunchKernelGGL(pair_distance_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden,
+                         M, dist);
+    }
+    hipLaunchKernelGGL(similarity_accumulate_kernel, dim3(1), dim3(1024), 0, s, dist, M, b, num_batches, metric,
+                       reinterpret_cast<double*>(ws + l.acc), sim);
+  }
+  return hip_status();
 }
 
 }  // namespace sere
@@ -530,72 +610,35 @@ size_t sere_similarity_workspace_bytes(const sere_config* cfg, int32_t batch_tok
 int sere_similarity(const sere_config* cfg, const void* calib, int32_t num_batches, int32_t batch_tokens,
                     const void* w_gate_up, const void* w_down, float* sim, void* workspace,
                     size_t workspace_bytes, void* hip_stream) {
-  int st = check_config(cfg);
-  if (st != SERE_OK) return st;
-  st = check_similarity_sizes(*cfg, num_batches, batch_tokens);
-  if (st != SERE_OK) return st;
-  PtrCheck pc;
-  pc.need(calib);
-  pc.need(w_gate_up);
-  pc.need(w_down);
-  pc.need(sim);
-  if (pc.status != SERE_OK) return pc.status;
-  const SimLayout l = make_sim_layout(*cfg, batch_tokens);
-  if (workspace == nullptr) return SERE_ERR_NULL_PTR;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SERE_ERR_MISALIGNED;
-  if (workspace_bytes < l.total) return SERE_ERR_WORKSPACE_TOO_SMALL;
+  return similarity(cfg, calib, num_batches, batch_tokens, w_gate_up, w_down, kCkaLinear, 0.0, 0.0, sim, workspace,
+                    workspace_bytes, hip_stream);
+}
 
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  char* ws = static_cast<char*>(workspace);
-  const int M = cfg->num_experts, n = batch_tokens;
-  FfnArgs f{};
-  f.w_gate_up = w_gate_up;
-  f.w_down = w_down;
-  f.sorted_token = reinterpret_cast<int32_t*>(ws + l.sorted_token);
-  f.work_expert = reinterpret_cast<int32_t*>(ws + l.work_expert);
-  f.work_off = reinterpret_cast<int32_t*>(ws + l.work_off);
-  f.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
-  f.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
-  f.h = reinterpret_cast<float*>(ws + l.h);
-  f.y = reinterpret_cast<float*>(ws + l.y);
-  f.T = n;
-  f.dh = cfg->hidden;
-  f.dm = cfg->inter;
-  f.M = M;
-  f.K = 1;
-  f.n_sh = 0;
-  f.ksplit = l.ksplit;
-  f.rows = l.rows;
-  f.split_h = wants_split_h(*cfg);
-  hipLaunchKernelGGL(similarity_worklist_kernel, dim3((M * n + 255) / 256), dim3(256), 0, s, M, n,
-                     const_cast<int32_t*>(f.sorted_token), const_cast<int32_t*>(f.work_expert),
-                     const_cast<int32_t*>(f.work_off), const_cast<int32_t*>(f.work_cnt),
-                     const_cast<int32_t*>(f.n_work));
-  const size_t eb = cfg->dtype == SERE_F32 ? 4 : 2;
-  const int metric = (cfg->flags & SERE_FLAG_SIM_COSINE)
-                         ? kMetricCosine
-                         : ((cfg->flags & SERE_FLAG_SIM_CKA_LINEAR) ? kMetricCkaLinear : kMetricFrobenius);
-  double* dist = reinterpret_cast<double*>(ws + l.dist);
-  for (int b = 0; b < num_batches; ++b) {
-    f.hidden = static_cast<const char*>(calib) + static_cast<size_t>(b) * n * cfg->hidden * eb;
-    launch_gateup_down(cfg->dtype, cfg->inter, cfg->hidden, M, l.ksplit, f, s);
-    if (metric == kMetricCosine) {
-      hipLaunchKernelGGL(pair_cosine_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, M,
-                         dist);
-    } else if (metric == kMetricCkaLinear) {
-      double* gram = reinterpret_cast<double*>(ws + l.gram);
-      double* rowsum = reinterpret_cast<double*>(ws + l.rowsum);
-      hipLaunchKernelGGL(gram_kernel, dim3(n, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden, gram,
-                         rowsum);
-      hipLaunchKernelGGL(pair_hsic_kernel, dim3(M, M), dim3(256), 0, s, gram, rowsum, n, M, dist);
-    } else {
-      hipLaunchKernelGGL(pair_distance_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden,
-                         M, dist);
-    }
-    hipLaunchKernelGGL(similarity_accumulate_kernel, dim3(1), dim3(1024), 0, s, dist, M, b, num_batches, metric,
-                       reinterpret_cast<double*>(ws + l.acc), sim);
-  }
-  return hip_status();
+// cfg with the linear-CKA flag in place of any other metric flag (workspace layout and checks)
+static sere_config with_cka_flag(const sere_config* cfg) {
+  sere_config c = *cfg;
+  c.flags = (c.flags & ~SERE_FLAG_SIM_COSINE) | SERE_FLAG_SIM_CKA_LINEAR;
+  return c;
+}
+
+size_t sere_similarity_cka_workspace_bytes(const sere_config* cfg, int32_t batch_tokens) {
+  if (cfg == nullptr) return 0;
+  const sere_config c = with_cka_flag(cfg);
+  return sere_similarity_workspace_bytes(&c, batch_tokens);
+}
+
+int sere_similarity_cka(const sere_config* cfg, const void* calib, int32_t num_batches, int32_t batch_tokens,
+                        const void* w_gate_up, const void* w_down, int32_t kernel, double param0, double param1,
+                        float* sim, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (cfg == nullptr) return SERE_ERR_NULL_PTR;
+  if (kernel != SERE_CKA_LINEAR && kernel != SERE_CKA_RBF && kernel != SERE_CKA_POLY) return SERE_ERR_BAD_KERNEL;
+  if (kernel == SERE_CKA_RBF && !(std::isfinite(param0) && param0 > 0.0)) return SERE_ERR_BAD_KERNEL;
+  if (kernel == SERE_CKA_POLY &&
+      !(std::isfinite(param0) && param1 >= 1.0 && param1 <= 16.0 && param1 == std::floor(param1)))
+    return SERE_ERR_BAD_KERNEL;
+  const sere_config c = with_cka_flag(cfg);
+  return similarity(&c, calib, num_batches, batch_tokens, w_gate_up, w_down, kernel, param0, param1, sim, workspace,
+                    workspace_bytes, hip_stream);
 }
 
 int sere_stage_timing(int enable) {
@@ -638,6 +681,7 @@ const char* sere_status_string(int status) {
     case SERE_ERR_BAD_FLAGS: return "flags has an unknown bit";
     case SERE_ERR_NONFINITE_THRESHOLD: return "threshold is NaN or infinite";
     case SERE_ERR_HIP: return "a HIP call reported an error";
+    case SERE_ERR_BAD_KERNEL: return "unknown CKA kernel, or a kernel parameter outside its range";
     default: return "unknown status";
   }
 }

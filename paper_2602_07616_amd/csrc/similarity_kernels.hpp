@@ -105,8 +105,11 @@ __global__ __launch_bounds__(256) void pair_cosine_kernel(const float* __restric
 // sums.  Entries (i, j) and (j, i) are formed by the same operations in the same order, so the
 // matrix is symmetric to the bit.  grid (n, M), 256 threads: wavefront w takes j = w, w+4, ...;
 // fp64 accumulation.
+// With `diag` (RBF and polynomial kernels) the diagonal <A_e[i], A_e[i]> goes there and the row
+// sums are left to gram_transform_kernel (rowsum == nullptr).
 __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ y, int ksplit, int rows, int n, int dh,
-                                                   double* __restrict__ gram, double* __restrict__ rowsum) {
+                                                   double* __restrict__ gram, double* __restrict__ rowsum,
+                                                   double* __restrict__ diag) {
   __shared__ double part[4];
   const int i = blockIdx.x, e = blockIdx.y;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -128,11 +131,54 @@ __global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ y, 
       dot += (ax * bx + ay * by) + (az * bz + aw * bw);
     }
     dot = wave_sum(dot);
-    if (j == i) dot = 0.0;
+    if (j == i) {
+      if (diag != nullptr && lane == 0) diag[static_cast<size_t>(e) * n + i] = dot;
+      dot = 0.0;
+    }
     if (lane == 0) gram[(static_cast<size_t>(e) * n + i) * n + j] = dot;
     row += dot;
   }
   if (lane == 0) part[wave] = row;
+  __syncthreads();
+  if (threadIdx.x == 0 && rowsum != nullptr)
+    rowsum[static_cast<size_t>(e) * n + i] = (part[0] + part[1]) + (part[2] + part[3]);
+}
+
+constexpr int kCkaLinear = 0, kCkaRbf = 1, kCkaPoly = 2;  // SERE_CKA_* of the header
+
+// The other two kernels of that appendix, from the linear Gram matrix G (off-diagonal entries in
+// `gram`, diagonal in `diag`), in place, with the row sums of the result:
+//   RBF:        K_ij = exp(-(G_ii + G_jj - 2 G_ij) / (2 sigma^2)),  sigma = p0
+//   polynomial: K_ij = (G_ij + c)^d,  c = p0, d = degree (repeated multiplication)
+// The diagonal stays 0 (the HSIC estimator ignores it); (i, j) and (j, i) take the same operations
+// on the same values, so the matrix stays symmetric to the bit.  grid (n, M), 256 threads.
+__global__ __launch_bounds__(256) void gram_transform_kernel(double* __restrict__ gram,
+                                                             const double* __restrict__ diag, int n, int kernel,
+                                                             double p0, int degree,
+                                                             double* __restrict__ rowsum) {
+  __shared__ double part[4];
+  const int i = blockIdx.x, e = blockIdx.y;
+  double* row = gram + (static_cast<size_t>(e) * n + i) * n;
+  const double* d = diag + static_cast<size_t>(e) * n;
+  const double di = d[i];
+  double sum = 0.0;
+  for (int j = threadIdx.x; j < n; j += 256) {
+    double v = 0.0;
+    if (j != i) {
+      const double g = row[j];
+      if (kernel == kCkaRbf) {
+        v = exp(-((di + d[j]) - 2.0 * g) / (2.0 * p0 * p0));
+      } else {
+        const double base = g + p0;
+        v = base;
+        for (int k = 1; k < degree; ++k) v *= base;
+      }
+    }
+    row[j] = v;
+    sum += v;
+  }
+  sum = wave_sum(sum);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
   __syncthreads();
   if (threadIdx.x == 0) rowsum[static_cast<size_t>(e) * n + i] = (part[0] + part[1]) + (part[2] + part[3]);
 }

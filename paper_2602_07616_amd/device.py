@@ -34,11 +34,12 @@ def to_host(t, dtype: int) -> np.ndarray:
     return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def similarity_on_device(wl: Workload, weights=None, device="cuda", metric="frobenius"):
+def similarity_on_device(wl: Workload, weights=None, device="cuda", metric="frobenius", cka=None):
     """Expert-similarity matrix of the workload's layer from its calibration
     tokens, computed by the library (sere_similarity); returns a device fp32 [M, M]
     tensor.  `weights` = (router_w, w_gate_up, w_down, ...) already on the device.
-    metric: "frobenius" | "cosine" | "cka_linear"."""
+    metric: "frobenius" | "cosine" | "cka_linear"; or cka = (kernel, param0, param1) with kernel
+    "linear" | "rbf" | "poly" for sere_similarity_cka."""
     import torch
     sp = wl.spec
     n_batches, n_tokens = wl.calib.shape[0], wl.calib.shape[1]
@@ -49,8 +50,15 @@ def similarity_on_device(wl: Workload, weights=None, device="cuda", metric="frob
     dn = to_device(wl.w_down, sp.dtype, device) if weights is None else weights[2]
     calib = to_device(wl.calib, sp.dtype, device)
     sim = torch.empty((sp.experts, sp.experts), dtype=torch.float32, device=device)
-    ws = torch.empty(B.sere_similarity_workspace_bytes(cfg, n_tokens), dtype=torch.uint8, device=device)
-    B.sere_similarity(cfg, calib, n_batches, n_tokens, gu, dn, sim, ws)
+    if cka is not None:
+        kernel, p0, p1 = cka
+        ws = torch.empty(B.sere_similarity_cka_workspace_bytes(cfg, n_tokens), dtype=torch.uint8, device=device)
+        B.sere_similarity_cka(cfg, calib, n_batches, n_tokens, gu, dn,
+                              {"linear": B.SERE_CKA_LINEAR, "rbf": B.SERE_CKA_RBF, "poly": B.SERE_CKA_POLY}[kernel],
+                              p0, p1, sim, ws)
+    else:
+        ws = torch.empty(B.sere_similarity_workspace_bytes(cfg, n_tokens), dtype=torch.uint8, device=device)
+        B.sere_similarity(cfg, calib, n_batches, n_tokens, gu, dn, sim, ws)
     torch.cuda.synchronize()
     return sim
 

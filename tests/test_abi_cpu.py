@@ -40,7 +40,7 @@ def test_workspace_size_and_status_strings():
     c = good(); c.num_shared = 2
     assert B.sere_workspace_bytes(c) > B.sere_workspace_bytes(good())
     assert B.load().sere_workspace_bytes(None) == 0
-    for s in range(0, -10, -1):
+    for s in range(0, -11, -1):
         assert B.sere_status_string(s) and B.sere_status_string(s) != "unknown status"
     assert B.sere_status_string(-99) == "unknown status"
 
@@ -174,3 +174,26 @@ def test_header_is_plain_c_and_links(tmp_path):
                     str(src), "-o", str(exe), "-L", lib_dir, "-l:" + os.path.basename(B.LIB_PATH),
                     "-Wl,-rpath," + lib_dir, "-Wl,--unresolved-symbols=ignore-in-shared-libs"], check=True)
     assert exe.exists()
+
+
+def test_cka_kernel_parameters_validated():
+    """sere_similarity_cka rejects unknown kernels and parameters outside their range before anything
+    is enqueued; the metric bits of cfg.flags play no part."""
+    lib = B.load()
+    cfg = good()
+    c = ctypes.byref(cfg)
+
+    def call(kernel, p0, p1, n=64, ws_bytes=0):
+        return lib.sere_similarity_cka(c, FAKE, 1, n, FAKE, FAKE, kernel, p0, p1, FAKE, FAKE, ws_bytes, None)
+    for kernel, p0, p1 in ((3, 1.0, 1.0), (-1, 1.0, 1.0), (B.SERE_CKA_RBF, 0.0, 0.0), (B.SERE_CKA_RBF, -1.0, 0.0),
+                           (B.SERE_CKA_RBF, float("nan"), 0.0), (B.SERE_CKA_POLY, 1.0, 0.0),
+                           (B.SERE_CKA_POLY, 1.0, 17.0), (B.SERE_CKA_POLY, 1.0, 2.5),
+                           (B.SERE_CKA_POLY, float("inf"), 2.0)):
+        assert call(kernel, p0, p1) == B.SERE_ERR_BAD_KERNEL, (kernel, p0, p1)
+    for kernel, p0, p1 in ((B.SERE_CKA_LINEAR, 0.0, 0.0), (B.SERE_CKA_RBF, 0.5, 0.0), (B.SERE_CKA_POLY, -1.0, 3.0)):
+        assert call(kernel, p0, p1) == B.SERE_ERR_WORKSPACE_TOO_SMALL      # accepted up to the workspace check
+        assert call(kernel, p0, p1, n=3) == B.SERE_ERR_BAD_SHAPE
+    assert B.sere_similarity_cka_workspace_bytes(cfg, 64) > B.sere_similarity_workspace_bytes(cfg, 64)
+    cfg.flags = B.SERE_FLAG_SIM_COSINE
+    assert call(B.SERE_CKA_RBF, 0.5, 0.0) == B.SERE_ERR_WORKSPACE_TOO_SMALL
+    assert lib.sere_similarity_cka(None, FAKE, 1, 64, FAKE, FAKE, 0, 0.0, 0.0, FAKE, FAKE, 0, None) == B.SERE_ERR_NULL_PTR

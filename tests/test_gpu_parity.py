@@ -549,6 +549,37 @@ def test_similarity_cka_linear_parity(dev, name):
         assert min(twins) > 0.9
 
 
+@pytest.mark.parametrize("name", ["tiny", "cka_bf16"])
+def test_similarity_cka_rbf_and_polynomial_parity(dev, name):
+    """sere_similarity_cka with the RBF and the polynomial kernel against the oracle's; the kernel
+    parameters are set from the data (sigma = a median distance between outputs of one expert,
+    c = a mean squared output norm) so that the Gram matrices are neither flat nor saturated."""
+    if name == "tiny":
+        wl = get_workload("tiny")
+    else:
+        wl = wk.make_workload(wk.custom_spec("cka_bf16", wk.BF16, 256, 12, 2, 192, 0, 4, 6300, twin_src=0, twin_dst=6,
+                                             twin_n=6, calib_batches=2, calib_tokens=40))
+    sp = wl.spec
+    n = wl.calib.shape[1]
+    a0 = oracle.moe_layer(wl.calib[0], wl.w_gate_up, wl.w_down, None, None, sp.dtype,
+                          np.zeros((n, 1), dtype=np.int32), np.ones((n, 1)))
+    sq = np.sum((a0[:, None, :] - a0[None, :, :]) ** 2, axis=2)
+    sigma = float(np.sqrt(np.median(sq[sq > 0])))
+    c = float(np.mean(np.sum(a0 * a0, axis=1)))
+    tol = 1e-5 if sp.dtype == wk.F32 else 5e-3
+    for kernel, p0, p1 in (("rbf", sigma, 0.0), ("poly", c, 3.0), ("linear", 0.0, 0.0)):
+        print(f"cka {kernel} {name} p0={p0:.4g}", flush=True)
+        got = dev.similarity_on_device(wl, cka=(kernel, p0, p1)).cpu().numpy()
+        want = oracle.similarity_cka(wl.calib, wl.w_gate_up, wl.w_down, sp.dtype, kernel, p0, p1)
+        err = np.abs(got - want).max()
+        print(f"  max |cka - oracle| = {err:.3e}, range [{want.min():.3f}, {want.max():.3f}]", flush=True)
+        assert err <= tol, (kernel, err)
+        assert np.array_equal(got, got.T)
+        assert np.allclose(np.diag(got), 1.0, atol=1e-6)
+        if sp.twin_n:
+            assert min(got[sp.twin_src + i, sp.twin_dst + i] for i in range(sp.twin_n)) > 0.9
+
+
 def test_similarity_with_long_calibration_batches(dev):
     """100 calibration tokens per batch: every expert is a work item of 100 rows, served in passes of
     up to 128 (gate/up) and 64 (down) token rows."""
