@@ -369,10 +369,13 @@ struct RouteArgs {
   int32_t* work_cnt;        // [max items] rows of the item (1 .. kItemRows)
   int32_t* n_work;          // [2]: number of items; 1 if the FFN kernels are to cut them fine
   int fine_items;           // ... which they do while there are at most this many items
+  int topk_threads;         // threads of a workgroup that take part in the top-K merge (256 or 1024)
   int item_rows;            // rows per work item: kItemRows, or twice that for batches with many rows per expert
 };
 
 constexpr int kRouteThreads = 1024;
+constexpr int kTopkThreadsMulti = 256;  // threads of a workgroup that merge lists when a few workgroups share the batch
+constexpr int kTopkMaxSmallGroups = 16; // ... up to this many workgroups (each pays a device-scope fence)
 constexpr int kRouteWaves = kRouteThreads / kWave;
 constexpr int kItemRows = 32;                     // rows of the sorted slot list per FFN work item (RouteArgs::item_rows may double it)
 constexpr int kIdsInLds = 4096;                   // slots whose ids a lone workgroup keeps in LDS
@@ -650,15 +653,19 @@ __global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const uint64_
                                                                    RouteArgs p) {
   __shared__ RouteShared s;
   constexpr int NC = LP;  // the similarity scan uses the same bound M <= 16*LP
-  constexpr int kTokens = kRouteThreads / LP;
+  // tokens per workgroup: the first p.topk_threads threads merge lists (the host's choice: all 1024,
+  // or 256 -- one wavefront per SIMD, the merge being bound by the vector ALU -- so that a batch
+  // shared by several workgroups spreads over more compute units)
+  const int group_tokens = p.topk_threads / LP;
   SimPrefetch<NC> pf;
   prefetch_sim(p, pf);
   const int nlists = (p.M + 15) >> 4;
-  const int t = blockIdx.x * kTokens + threadIdx.x / LP;
+  const int t = blockIdx.x * group_tokens + threadIdx.x / LP;
   const bool lone = gridDim.x == 1 && p.T * p.K <= kIdsInLds;
-  const bool has = t < p.T;
-  const int first_of_wave = blockIdx.x * kTokens + (threadIdx.x >> 6) * (kWave / LP);
-  if (first_of_wave < p.T) {  // wave-uniform: the wavefront has a token
+  const bool in_group = static_cast<int>(threadIdx.x) < group_tokens * LP;
+  const bool has = in_group && t < p.T;
+  const int first_of_wave = blockIdx.x * group_tokens + (threadIdx.x >> 6) * (kWave / LP);
+  if (static_cast<int>(threadIdx.x & ~63u) < group_tokens * LP && first_of_wave < p.T) {  // wave-uniform: the wavefront has a token
     const size_t tt = has ? t : 0;
     topk_merge<LP, KS, KEEP>(list_key + tt * nlists * 16, list_id + tt * nlists * 16, has, nlists, topk_ids + tt * p.K,
                        topk_w + tt * p.K, lone ? s.ids8 + tt * p.K : nullptr, p.K);

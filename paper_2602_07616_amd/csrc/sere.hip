@@ -219,6 +219,13 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
   r.work_off = reinterpret_cast<int32_t*>(ws + l.work_off);
   r.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
   r.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
+  // top-K: one workgroup if the batch fits its 1024 threads; else groups of 256 threads while that
+  // gives at most kTopkMaxSmallGroups workgroups; else groups of 1024
+  const int lists = (c.num_experts + 15) / 16;
+  const long long merge_threads = static_cast<long long>(c.num_tokens) * (lists <= 4 ? 4 : (lists <= 8 ? 8 : 16));
+  r.topk_threads = (merge_threads > kRouteThreads && merge_threads <= kTopkMaxSmallGroups * kTopkThreadsMulti)
+                       ? kTopkThreadsMulti
+                       : kRouteThreads;
   r.fine_items = kFineCutBlocks / (c.inter / (2 * kGateUpJ * kWavesPerBlock));
   // many rows per expert on average (prefill-sized batches): items of 64 or 128 rows, served in one
   // pass over the weights each
@@ -268,7 +275,7 @@ static int launch_route(const sere_config& c, const Pointers& p, bool with_topk,
     const int lists = (c.num_experts + 15) / 16;
     const int lp = lists <= 4 ? 4 : (lists <= 8 ? 8 : 16);
     const bool small_k = c.top_k <= 2 * lp;
-    const dim3 grid((c.num_tokens * lp + kRouteThreads - 1) / kRouteThreads);
+    const dim3 grid((c.num_tokens * lp + p.route.topk_threads - 1) / p.route.topk_threads);
 #define SERE_LAUNCH_TOPK(LP, KS, KEEP)                                                                          \
   launch_stage(SERE_STAGE_ROUTE, s, topk_route_kernel<LP, KS, KEEP>, grid, dim3(kRouteThreads), p.list_key, \
                p.list_id, p.topk_ids, p.topk_w, p.ticket, p.route)
