@@ -325,7 +325,8 @@ __device__ __forceinline__ void topk_merge(const uint64_t* __restrict__ list_key
     for (int c = 0; c < KS; ++c)
       if (k == l + LP * c) mysel[c] = val;
     if (l == 0 && active) {
-      ids[k] = static_cast<int32_t>(wid);
+      // a device-scope store: with several workgroups the ids are read by another one of this launch
+      __hip_atomic_store(ids + k, static_cast<int32_t>(wid), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (ids8 != nullptr) ids8[k] = static_cast<uint8_t>(wid);
     }
   }
@@ -374,8 +375,11 @@ struct RouteArgs {
 };
 
 constexpr int kRouteThreads = 1024;
-constexpr int kTopkThreadsMulti = 256;  // threads of a workgroup that merge lists when a few workgroups share the batch
-constexpr int kTopkMaxSmallGroups = 16; // ... up to this many workgroups (each pays a device-scope fence)
+constexpr int kTopkThreadsMulti = 256;   // threads of a workgroup that merge lists when several workgroups share the batch
+constexpr int kTopkLoneThreads = 512;    // one workgroup serves the whole batch up to this many merging threads
+                                         // (measured: 1024 threads on one compute unit take 14.5 us, four
+                                         // workgroups of 256 take 11.6 us)
+constexpr int kTopkMaxSmallGroups = 64;  // groups of 256 threads up to this many workgroups, of 1024 beyond
 constexpr int kRouteWaves = kRouteThreads / kWave;
 constexpr int kItemRows = 32;                     // rows of the sorted slot list per FFN work item (RouteArgs::item_rows may double it)
 constexpr int kIdsInLds = 4096;                   // slots whose ids a lone workgroup keeps in LDS
@@ -440,8 +444,10 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
   const int A = p.T * K;
   // ids read from memory may be a caller's (sere_reroute): clamped into [0, M) so that an id outside
   // that range, a broken precondition, cannot send any access out of bounds
+  // (device-scope loads: the ids may have been written by other workgroups of this launch)
   auto id_at = [&](int a) -> int {
-    return IDS_IN_LDS ? static_cast<int>(s.ids8[a]) : min(max(p.topk_ids[a], 0), M - 1);
+    return IDS_IN_LDS ? static_cast<int>(s.ids8[a])
+                      : min(max(__hip_atomic_load(p.topk_ids + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), 0), M - 1);
   };
 
   if (tid < SERE_MAX_EXPERTS) {
@@ -676,12 +682,18 @@ __global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const uint64_
     return;
   }
   if (gridDim.x > 1) {
-    __threadfence();  // this workgroup's top-K results are visible device-wide ...
+    // The ids were stored at device scope (written through): once those stores have been
+    // acknowledged they are visible to every workgroup, with no cache write-back or invalidation
+    // (a device-scope fence costs this kernel several microseconds on this multi-die part).  The
+    // workgroup then takes its ticket; the one that takes the last ticket has, through the order of
+    // the tickets, every other workgroup's acknowledged stores before it, and reads the ids with
+    // device-scope loads.
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
-    if (threadIdx.x == 0) s.flag = atomicAdd(ticket, 1) == static_cast<int>(gridDim.x) - 1;
+    if (threadIdx.x == 0)
+      s.flag = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == static_cast<int>(gridDim.x) - 1;
     __syncthreads();
-    if (!s.flag) return;  // ... before the last workgroup reads them
-    __threadfence();
+    if (!s.flag) return;
   } else {
     __syncthreads();
   }

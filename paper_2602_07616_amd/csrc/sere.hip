@@ -219,11 +219,12 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
   r.work_off = reinterpret_cast<int32_t*>(ws + l.work_off);
   r.work_cnt = reinterpret_cast<int32_t*>(ws + l.work_cnt);
   r.n_work = reinterpret_cast<int32_t*>(ws + l.n_work);
-  // top-K: one workgroup if the batch fits its 1024 threads; else groups of 256 threads while that
-  // gives at most kTopkMaxSmallGroups workgroups; else groups of 1024
+  // top-K: one workgroup (ids handed on through LDS) while the merge needs at most kTopkLoneThreads
+  // threads; else groups of 256 threads while that gives at most kTopkMaxSmallGroups workgroups;
+  // else groups of 1024
   const int lists = (c.num_experts + 15) / 16;
   const long long merge_threads = static_cast<long long>(c.num_tokens) * (lists <= 4 ? 4 : (lists <= 8 ? 8 : 16));
-  r.topk_threads = (merge_threads > kRouteThreads && merge_threads <= kTopkMaxSmallGroups * kTopkThreadsMulti)
+  r.topk_threads = (merge_threads > kTopkLoneThreads && merge_threads <= kTopkMaxSmallGroups * kTopkThreadsMulti)
                        ? kTopkThreadsMulti
                        : kRouteThreads;
   r.fine_items = kFineCutBlocks / (c.inter / (2 * kGateUpJ * kWavesPerBlock));
