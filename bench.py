@@ -165,6 +165,32 @@ class Runner:
             B.sere_stage_timing(False)
         return {s: (ms[s] * 1e3 / cnt[s] if cnt[s] else 0.0) for s in ms}
 
+    def plain_read(self, nbytes, launches=64):
+        """What the memory system delivers for a plain read of `nbytes` of this workload's own weight
+        bytes (library helper sere_stream_read): us per launch over back-to-back launches that each
+        read a different region of the resident copies, so that no cache can serve them."""
+        from paper_2602_07616_amd import binding as B
+        torch = self.torch
+        tensors = [l.w_gate_up for l in self.layers]
+        cap = tensors[0].numel() * tensors[0].element_size()
+        nbytes = min(int(nbytes) // 16 * 16, cap)
+        per = max(1, cap // nbytes)
+        regions = [(t, r * nbytes) for t in tensors for r in range(per)]
+        sink = torch.zeros(4, dtype=torch.int32, device=tensors[0].device)
+        flat = {id(t): t.view(torch.uint8).reshape(-1) for t in tensors}
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(self.stream):
+            for i in range(8):
+                t, off = regions[i % len(regions)]
+                B.sere_stream_read(flat[id(t)][off:], nbytes, sink, self.stream)
+            start.record(self.stream)
+            for i in range(launches):
+                t, off = regions[i % len(regions)]
+                B.sere_stream_read(flat[id(t)][off:], nbytes, sink, self.stream)
+            stop.record(self.stream)
+            stop.synchronize()
+        return start.elapsed_time(stop) * 1e3 / launches, nbytes
+
     def active(self, mode):
         """(n_active_before, n_active_after) of the current knobs."""
         l = self.layers[0]
@@ -270,6 +296,13 @@ def main():
                          "avg_launch_us": round(stages["down"], 2), "algorithmic_bytes_per_launch": down_bytes,
                          "traffic": traffic.get("down")},
                 "stage_us": {k: round(v, 2) for k, v in stages.items()}}
+    # what a plain read of as many bytes of the same weights takes on this machine (context for
+    # `frac`: the published peak is not attainable by any kernel), and a long read
+    read_us, read_bytes = run.plain_read(gateup_bytes)
+    long_us, long_bytes = run.plain_read(spec.experts * 2 * spec.hidden * spec.inter * eb, launches=16)
+    roofline["plain_read"] = {"bytes": read_bytes, "us": round(read_us, 2),
+                              "gb_per_s": round(read_bytes / read_us * 1e-3, 1),
+                              "long_read_bytes": long_bytes, "long_read_gb_per_s": round(long_bytes / long_us * 1e-3, 1)}
 
     result = {
         "metric": "us per MoE-layer decode step (SERE) + achieved HBM GB/s, SERE vs no-reroute",

@@ -275,6 +275,17 @@ int sere_similarity_cka(const sere_config *cfg, const void *calib, int32_t num_b
 int sere_stage_timing(int enable);
 int sere_stage_timing_read(double *total_ms, int32_t *launches);
 
+/*
+ * Benchmark helper: a plain streaming read of `bytes` bytes of device memory at
+ * `src` (a multiple of 16, 16-byte aligned) with non-temporal 128-bit loads,
+ * enqueued on the stream; nothing is computed but a checksum that is stored to
+ * sink[0] (device, 4 bytes) only if it equals a value no real data gives.  It
+ * measures what the memory system delivers for a read of that size on this
+ * machine, to set beside the published peak.  SERE_ERR_BAD_SHAPE for a size
+ * that is 0 or not a multiple of 16.
+ */
+int sere_stream_read(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char *sere_status_string(int status);
 

@@ -93,6 +93,8 @@ def load() -> ctypes.CDLL:
     lib.sere_similarity_cka.restype = ci
     lib.sere_similarity_cka.argtypes = [cfgp, vp, ctypes.c_int32, ctypes.c_int32, vp, vp, ctypes.c_int32,
                                         ctypes.c_double, ctypes.c_double, vp, vp, sz, vp]
+    lib.sere_stream_read.restype = ci
+    lib.sere_stream_read.argtypes = [vp, sz, vp, vp]
     lib.sere_stage_timing.restype = ci
     lib.sere_stage_timing.argtypes = [ci]
     lib.sere_stage_timing_read.restype = ci
@@ -234,6 +236,11 @@ def sere_similarity_cka(cfg, calib, num_batches, batch_tokens, w_gate_up, w_down
                                       _ptr(w_gate_up), _ptr(w_down), kernel, float(param0), float(param1),
                                       _ptr(sim), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                       _stream(stream)))
+
+
+def sere_stream_read(src, nbytes: int, sink, stream=None) -> None:
+    """Plain streaming read of the first nbytes bytes of the tensor src (benchmark helper)."""
+    _check(load().sere_stream_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)))
 
 
 def sere_stage_timing(enable: bool) -> None:

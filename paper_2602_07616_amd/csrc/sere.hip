@@ -415,6 +415,26 @@ static int decode(const sere_config* cfg, const void* hidden, const void* router
   return hip_status();
 }
 
+// ------------------------------------------------------------ stream read ---
+constexpr int kStreamReadUnroll = 8;  // 128-bit loads in flight per thread
+
+// A workgroup reads 256 * kStreamReadUnroll consecutive 16-byte pieces, thread t the pieces
+// t, t + 256, ...: every load instruction of a wavefront covers 1 KB of consecutive memory.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t pieces,
+                                                          uint32_t* __restrict__ sink) {
+  const size_t base = static_cast<size_t>(blockIdx.x) * 256 * kStreamReadUnroll + threadIdx.x;
+  u32x4 v[kStreamReadUnroll];
+#pragma unroll
+  for (int u = 0; u < kStreamReadUnroll; ++u) {
+    const size_t at = base + static_cast<size_t>(u) * 256;
+    v[u] = at < pieces ? __builtin_nontemporal_load(src + at) : u32x4{0u, 0u, 0u, 0u};
+  }
+  uint32_t acc = 0;
+#pragma unroll
+  for (int u = 0; u < kStreamReadUnroll; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  if (acc == 0x9e3779b9u && blockIdx.x == 0xfffffffeu) sink[0] = acc;  // keeps the loads alive; never true
+}
+
 // ------------------------------------------------------------- similarity ---
 struct SimLayout {
   size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, gram, rowsum, diag, total;
@@ -647,6 +667,19 @@ int sere_similarity_cka(const sere_config* cfg, const void* calib, int32_t num_b
   const sere_config c = with_cka_flag(cfg);
   return similarity(&c, calib, num_batches, batch_tokens, w_gate_up, w_down, kernel, param0, param1, sim, workspace,
                     workspace_bytes, hip_stream);
+}
+
+int sere_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream) {
+  if (src == nullptr || sink == nullptr) return SERE_ERR_NULL_PTR;
+  if (!aligned16(src)) return SERE_ERR_MISALIGNED;
+  if (bytes == 0 || bytes % 16 != 0) return SERE_ERR_BAD_SHAPE;
+  const size_t pieces = bytes / 16;
+  const size_t per_block = static_cast<size_t>(256) * kStreamReadUnroll;
+  const size_t blocks = (pieces + per_block - 1) / per_block;
+  if (blocks > 0x7fffffffull) return SERE_ERR_BAD_SHAPE;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), static_cast<const u32x4*>(src), pieces, sink);
+  return hip_status();
 }
 
 int sere_stage_timing(int enable) {
