@@ -66,12 +66,20 @@ def elementwise_bound(want, dtype):
 
 
 def check_output(got, want, dtype, what=""):
-    _, rel = TOL[dtype]
+    max_abs, rel = TOL[dtype]
     diff = np.abs(got - want)
     err = diff.max()
     rl2 = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
     assert np.isfinite(got).all(), what
-    worst = (diff / elementwise_bound(want, dtype)).max()
+    bound = elementwise_bound(want, dtype)
+    wide = int((bound > max_abs).sum())
+    if wide:
+        # how many elements were judged by the half-ulp bound instead of the stated one (|y| >= 8),
+        # and how many of those actually needed it
+        used = int(((diff > max_abs) & (bound > max_abs)).sum())
+        print(f"   {what}: {wide} of {want.size} elements have |y| >= 8 (bound 1.25 x half an ulp); "
+              f"{used} of them exceed {max_abs:g}", flush=True)
+    worst = (diff / bound).max()
     assert worst <= 1.0 and rl2 <= rel, f"{what}: max_abs {err:.3e} rel_l2 {rl2:.3e} worst/bound {worst:.2f}"
     return err, rl2
 
@@ -103,8 +111,9 @@ def oracle_output(wl, ids, weights, key, tokens=None):
 
 
 FULL = ["tiny", "qwen3_b32", "qwen3_b128", "dsv2lite_b64", "mixtral_b64", "qwen15_b32"]
-# layers whose full oracle output is too slow to compute for every token
-SAMPLED = {"mixtral_b64": [0, 7, 13, 21, 30, 42, 55, 63]}
+# layers whose oracle output would be computed on sampled tokens only: none (the Mixtral-shaped
+# layer takes the oracle about half a minute for all 64 tokens)
+SAMPLED = {}
 
 
 def grid_of(name):
@@ -194,7 +203,7 @@ def test_batch_sweep_decode(dev, T):
         layer.run_decode()
         ref = oracle_route(wl, sim, S, rho, ("sweep", T))
         check_routing(layer.routing_to_host(), ref, layer.cfg)
-        tokens = None if T <= 64 else list(range(0, T, 8))
+        tokens = None                       # every token, also at T = 256
         want = oracle_output(wl, ref.rerouted_ids, ref.topk_weights, ("sweep", T), tokens)
         got = layer.out_to_host_f64()
         check_output(got if tokens is None else got[tokens], want, wl.spec.dtype, f"T={T} S={S}")
@@ -310,6 +319,81 @@ def test_edge_cases(dev, case):
     layer.out.zero_()
     layer.run_decode(with_outputs=False)
     assert (layer.out == a).all()
+
+
+def plant_routing(wl, experts_of_token):
+    """Make the router's choice explicit: router row e becomes the unit vector of coordinate e and
+    token t's first M coordinates hold K + 1 - rank for its designated experts (0 elsewhere), so
+    that logit[t, e] is exactly that value and the ordered top-K of token t is experts_of_token[t].
+    All other coordinates of the hidden states keep their random values."""
+    spec = wl.spec
+    M = spec.experts
+    router = np.zeros((M, spec.hidden), dtype=np.float32)
+    router[np.arange(M), np.arange(M)] = 1.0
+    wl.router_w[:] = wk.to_storage(router, spec.dtype)
+    head = np.zeros((spec.tokens, M), dtype=np.float32)
+    for t, experts in enumerate(experts_of_token):
+        for rank, e in enumerate(experts):
+            head[t, e] = len(experts) + 1 - rank
+    wl.hidden[:, :M] = wk.to_storage(head, spec.dtype)
+
+
+def pairs_with_counts(counts):
+    """Two distinct experts per token such that expert e owns counts[e] slots in total (sum even)."""
+    flat = np.repeat(np.arange(len(counts)), counts)
+    half = len(flat) // 2
+    pairs = [(int(flat[i]), int(flat[i + half])) for i in range(half)]
+    assert all(a != b for a, b in pairs)
+    return pairs
+
+
+# bf16 layers with d_m >= 4096: the intermediate h travels as a high and a low bf16 plane and the
+# down projection multiplies both.  Experts own 1, 16, 17, 32, 33 and more rows (one tile, two
+# tiles, more than one work item); few experts -> the fine cut of the FFN kernels, many -> the coarse one.
+WIDE = [
+    # d_h, d_m, shared, slots per expert
+    (256, 4096, 0, [1, 16, 17, 32, 33, 21]),
+    (320, 4160, 1, [1, 16, 17, 32, 33, 21]),
+    (256, 4096, 1, [1, 16, 17, 32, 33, 40, 2, 3] + [5] * 16 + [1, 1]),
+    (320, 4160, 0, [1, 16, 17, 32, 33, 40, 2, 3] + [5] * 16 + [1, 1]),
+]
+
+
+@pytest.mark.parametrize("case", WIDE, ids=lambda c: f"{c[0]}x{c[1]}x{c[2]}x{len(c[3])}")
+def test_wide_experts_with_two_plane_intermediate(dev, case):
+    dh, dm, n_sh, counts = case
+    M, K = len(counts), 2
+    pairs = pairs_with_counts(counts)
+    T = len(pairs)
+    print(f"wide experts d_h={dh} d_m={dm} shared={n_sh} M={M} T={T}", flush=True)
+    spec = wk.custom_spec(f"wide{dh}x{dm}x{M}", wk.BF16, dh, M, K, dm, n_sh, T, 9100 + dm + M,
+                          calib_batches=1, calib_tokens=4)
+    wl = wk.make_workload(spec)
+    plant_routing(wl, pairs)
+    sim = pins.rand_sim(9100 + M, M)
+    layer = dev.DeviceLayer.from_workload(wl, sim, K, 0.0)
+    # the cut the routing kernel will choose: fine while the items are few
+    items = sum((c + 31) // 32 for c in counts) + n_sh * ((T + 31) // 32)
+    assert (items <= 2560 // (dm // 32)) == (M < 20)
+    for S, rho in ((K, 0.0), (1, 0.0), (1, 0.9)):
+        ref = oracle.layer(wl.hidden, wl.router_w, wl.w_gate_up, wl.w_down, wl.shared_gate_up,
+                           wl.shared_down, wk.BF16, K, sim, S, rho)
+        assert ref.min_gap >= 1.0
+        assert np.array_equal(ref.topk_ids, np.asarray(pairs, dtype=np.int32))
+        if S == K:
+            assert ref.count_after.tolist() == counts
+            sizes = set(ref.count_after.tolist())
+            assert {1, 16, 17, 32, 33} <= sizes
+        layer.set_knobs(S, rho)
+        layer.out.zero_()
+        layer.run_decode()
+        check_routing(layer.routing_to_host(), ref, layer.cfg)
+        err = check_output(layer.out_to_host_f64(), ref.out_sere, wk.BF16, f"wide S={S} rho={rho}")
+        print(f"   S={S} rho={rho}: rows per expert {sorted(set(ref.count_after.tolist()))}, "
+              f"max_abs {err[0]:.2e} rel_l2 {err[1]:.2e}", flush=True)
+    layer.out.zero_()
+    layer.run_baseline()
+    check_output(layer.out_to_host_f64(), ref.out_base, wk.BF16, "wide baseline")
 
 
 def _random_configs(n=18, seed=20260):
