@@ -58,6 +58,8 @@ extern "C" {
 #define SERE_ERR_HIP (-9)                 /* a HIP launch reported an error              */
 #define SERE_ERR_BAD_KERNEL (-10)         /* sere_similarity_cka: unknown kernel or a
                                              parameter outside its range                 */
+#define SERE_ERR_SCRATCH_TOO_SMALL (-11)  /* sere_moe_decode_static: the configuration needs
+                                             more than SERE_STATIC_SCRATCH_BYTES         */
 
 /* sere_config.flags */
 #define SERE_FLAG_RESIDUAL 1 /* sere_moe_decode[_baseline]: out = hidden + layer(hidden), the
@@ -193,6 +195,32 @@ int sere_moe_decode_baseline(const sere_config *cfg, const void *hidden, const v
                              const void *shared_gate_up, const void *shared_down, void *out,
                              const sere_route_out *dbg, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
+
+/*
+ * sere_moe_decode for callers that cannot allocate device memory or hand over
+ * a workspace: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * results as sere_moe_decode, minus the workspace: the intermediate buffers
+ * live in a device array of SERE_STATIC_SCRATCH_BYTES bytes that is part of
+ * the library image (every GPU the library runs on holds its own copy until
+ * the process ends).  The call allocates nothing and frees nothing.
+ *   - SERE_ERR_SCRATCH_TOO_SMALL if sere_workspace_bytes(cfg) exceeds
+ *     SERE_STATIC_SCRATCH_BYTES (the five reference layer shapes up to a
+ *     Mixtral-shaped layer at batch 64 fit); nothing is enqueued then.
+ *   - The device that `hip_stream` belongs to must be the current device.  The
+ *     first call on a device looks up that device's copy of the array (no
+ *     allocation, but a runtime query: make the first call outside graph
+ *     capture).
+ *   - All calls on one GPU share the one array, which keeps the last call's
+ *     contents (nothing in it needs to start at zero).  Two calls whose
+ *     execution overlaps on one GPU (different streams, or parallel branches
+ *     of a graph) race; calls ordered on one stream do not.
+ */
+#define SERE_STATIC_SCRATCH_BYTES (32u << 20)
+int sere_moe_decode_static(const sere_config *cfg, const void *hidden, const void *router_w,
+                           const void *w_gate_up, const void *w_down, const void *shared_gate_up,
+                           const void *shared_down, const float *sim, void *out,
+                           const sere_route_out *dbg, void *hip_stream);
 
 /*
  * Expert-similarity matrix of one layer from calibration tokens, with the

@@ -28,6 +28,8 @@ SERE_ERR_BAD_FLAGS = -7
 SERE_ERR_NONFINITE_THRESHOLD = -8
 SERE_ERR_HIP = -9
 SERE_ERR_BAD_KERNEL = -10
+SERE_ERR_SCRATCH_TOO_SMALL = -11
+SERE_STATIC_SCRATCH_BYTES = 32 << 20
 SERE_CKA_LINEAR, SERE_CKA_RBF, SERE_CKA_POLY = 0, 1, 2
 
 STAGES = ("router", "route", "gate_up", "down", "combine")
@@ -82,6 +84,8 @@ def load() -> ctypes.CDLL:
     lib.sere_reroute.argtypes = [cfgp, vp, vp, outp, vp, sz, vp]
     lib.sere_moe_decode.restype = ci
     lib.sere_moe_decode.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, outp, vp, sz, vp]
+    lib.sere_moe_decode_static.restype = ci
+    lib.sere_moe_decode_static.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, outp, vp]
     lib.sere_moe_decode_baseline.restype = ci
     lib.sere_moe_decode_baseline.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, outp, vp, sz, vp]
     lib.sere_similarity_workspace_bytes.restype = sz
@@ -204,6 +208,14 @@ def sere_moe_decode(cfg, hidden, router_w, w_gate_up, w_down, shared_gate_up, sh
                                   _ptr(w_down), _ptr(shared_gate_up), _ptr(shared_down), _ptr(sim),
                                   _ptr(out), _byref_or_null(o), _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def sere_moe_decode_static(cfg, hidden, router_w, w_gate_up, w_down, shared_gate_up, shared_down, sim,
+                           out, dbg, stream=None) -> None:
+    o = _route_out(dbg)
+    _check(load().sere_moe_decode_static(ctypes.byref(cfg), _ptr(hidden), _ptr(router_w), _ptr(w_gate_up),
+                                         _ptr(w_down), _ptr(shared_gate_up), _ptr(shared_down), _ptr(sim),
+                                         _ptr(out), _byref_or_null(o), _stream(stream)))
 
 
 def sere_moe_decode_baseline(cfg, hidden, router_w, w_gate_up, w_down, shared_gate_up,

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 
 #include "common.hpp"
 #include "ffn_generic.hpp"
@@ -348,13 +349,36 @@ static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p,
   launch_combine(c, l, p, f.hidden, out, s);
 }
 
+// --------------------------------------------------------- static scratch ---
+// Workspace of sere_moe_decode_static: part of the library image, one copy per GPU.  In host code
+// the array's name is only a handle for the runtime; the device address of the current GPU's copy
+// comes from hipGetSymbolAddress and is what every kernel argument is built from.
+static __device__ __align__(256) unsigned char scratch[SERE_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];  // per device, looked up on the first call with that device current
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SERE_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return SERE_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SERE_OK;
+}
+
 // wide experts: h keeps its bf16 rounding residual in a second plane (see decode())
 static int wants_split_h(const sere_config& c) { return (c.dtype == SERE_BF16 && c.inter >= 4096) ? 1 : 0; }
 
 static int decode(const sere_config* cfg, const void* hidden, const void* router_w, const void* w_gate_up,
                   const void* w_down, const void* shared_gate_up, const void* shared_down, const float* sim,
                   void* out, const sere_route_out* dbg, void* workspace, size_t workspace_bytes, void* stream,
-                  bool reroute) {
+                  bool reroute, bool static_workspace = false) {
   int st = check_config(cfg);
   if (st != SERE_OK) return st;
   PtrCheck pc;
@@ -371,6 +395,12 @@ static int decode(const sere_config* cfg, const void* hidden, const void* router
   check_route_out(pc, dbg);
   if (pc.status != SERE_OK) return pc.status;
   const Layout l = make_layout(*cfg);
+  if (static_workspace) {  // the library's own array instead of a caller's buffer
+    if (l.total > SERE_STATIC_SCRATCH_BYTES) return SERE_ERR_SCRATCH_TOO_SMALL;
+    st = static_scratch(&workspace);
+    if (st != SERE_OK) return st;
+    workspace_bytes = SERE_STATIC_SCRATCH_BYTES;
+  }
   st = check_workspace(l, workspace, workspace_bytes);
   if (st != SERE_OK) return st;
 
@@ -622,6 +652,14 @@ int sere_moe_decode(const sere_config* cfg, const void* hidden, const void* rout
                 workspace_bytes, hip_stream, true);
 }
 
+int sere_moe_decode_static(const sere_config* cfg, const void* hidden, const void* router_w,
+                           const void* w_gate_up, const void* w_down, const void* shared_gate_up,
+                           const void* shared_down, const float* sim, void* out, const sere_route_out* dbg,
+                           void* hip_stream) {
+  return decode(cfg, hidden, router_w, w_gate_up, w_down, shared_gate_up, shared_down, sim, out, dbg, nullptr, 0,
+                hip_stream, true, true);
+}
+
 int sere_moe_decode_baseline(const sere_config* cfg, const void* hidden, const void* router_w,
                              const void* w_gate_up, const void* w_down, const void* shared_gate_up,
                              const void* shared_down, void* out, const sere_route_out* dbg, void* workspace,
@@ -723,6 +761,7 @@ const char* sere_status_string(int status) {
     case SERE_ERR_NONFINITE_THRESHOLD: return "threshold is NaN or infinite";
     case SERE_ERR_HIP: return "a HIP call reported an error";
     case SERE_ERR_BAD_KERNEL: return "unknown CKA kernel, or a kernel parameter outside its range";
+    case SERE_ERR_SCRATCH_TOO_SMALL: return "the configuration needs more than SERE_STATIC_SCRATCH_BYTES of scratch";
     default: return "unknown status";
   }
 }

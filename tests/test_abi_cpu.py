@@ -40,7 +40,7 @@ def test_workspace_size_and_status_strings():
     c = good(); c.num_shared = 2
     assert B.sere_workspace_bytes(c) > B.sere_workspace_bytes(good())
     assert B.load().sere_workspace_bytes(None) == 0
-    for s in range(0, -11, -1):
+    for s in range(0, -12, -1):
         assert B.sere_status_string(s) and B.sere_status_string(s) != "unknown status"
     assert B.sere_status_string(-99) == "unknown status"
 
@@ -104,6 +104,28 @@ def test_bad_pointers_rejected():
     o.count_after = FAKE + 2
     assert lib.sere_route(ctypes.byref(good()), FAKE, FAKE, FAKE, ctypes.byref(o), FAKE, 1 << 40,
                           None) == B.SERE_ERR_MISALIGNED
+
+
+def test_static_scratch_entry_point_validates_before_touching_the_device():
+    """sere_moe_decode_static checks configuration, pointers and the size limit before it looks up
+    its scratch array (no GPU here, so only the error paths can be reached)."""
+    lib = B.load()
+
+    def call(cfg, ptr=FAKE, sim=FAKE):
+        return lib.sere_moe_decode_static(ctypes.byref(cfg), ptr, ptr, ptr, ptr, None, None, sim, FAKE, None, None)
+    bad = good(); bad.top_k = 500
+    assert call(bad) == B.SERE_ERR_BAD_TOPK
+    assert call(good(), ptr=0) == B.SERE_ERR_NULL_PTR
+    assert call(good(), ptr=FAKE + 4) == B.SERE_ERR_MISALIGNED
+    assert call(good(), sim=0) == B.SERE_ERR_NULL_PTR
+    big = good(); big.num_tokens = 4096
+    assert B.sere_workspace_bytes(big) > B.SERE_STATIC_SCRATCH_BYTES
+    assert call(big) == B.SERE_ERR_SCRATCH_TOO_SMALL
+    for name in ("qwen3_b32", "qwen3_b128", "dsv2lite_b64", "mixtral_b64", "qwen15_b32", "tiny"):
+        from paper_2602_07616_amd import workloads as wk
+        sp = wk.SPECS[name]
+        cfg = B.make_config(sp.tokens, sp.hidden, sp.experts, sp.top_k, sp.inter, sp.shared, sp.dtype, 1, 0.0)
+        assert 0 < B.sere_workspace_bytes(cfg) <= B.SERE_STATIC_SCRATCH_BYTES, name
 
 
 def test_similarity_validation():
