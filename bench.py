@@ -7,8 +7,12 @@ and weights are already resident in HBM.  Consecutive steps use different
 copies of the layer's weights so that the 256 MB last-level cache cannot serve
 them (a real model runs a different layer next).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
-                    [--S s] [--rho r] [--grid] [--sweep] [--rho-sweep] [--layers L] [--no-graph]
+The headline is the largest Qwen3-30B-A3B-shaped configuration (batch 128, S = 2, rho = 0);
+the same JSON line carries, under "configs", every layer shape of the task (and the
+Qwen1.5-MoE-shaped one) with its (S, rho) grid from the paper's main tables.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--only-headline]
+                    [--S s] [--rho r] [--sweep] [--rho-sweep] [--layers L] [--no-graph]
 """
 from __future__ import annotations
 
@@ -24,20 +28,30 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
-GRAPH_STEPS = 32          # decode steps captured in one HIP graph (see Runner.time)
+TARGET_FRAC = 0.70        # the task's target: whole SERE step at >= 70 % of that peak on the expert bytes read
+GRAPH_STEPS = 32          # decode steps captured in one HIP graph (fewer if fewer are timed; see Runner.time)
+STAT_REPLAYS = 8          # graph replays behind median / p10 / p90 (extra, untimed for `value`, if fewer were timed)
+HEADLINE = "qwen3_b128"
+ALL_WORKLOADS = ("qwen3_b128", "qwen3_b32", "dsv2lite_b64", "mixtral_b64", "qwen15_b32", "tiny")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
-# HBM bytes per launch (read + write) of the two FFN kernels, from rocprofv3 --pmc FETCH_SIZE
-# and --pmc WRITE_SIZE runs of `bench.py --only-sere --copy-calibration --no-graph`, each counter
-# scaled by what it reads for the plain 256 MiB copy in the same run (FETCH_SIZE x 1.9998,
-# WRITE_SIZE x 1.0000); commands and tables: profiles/sere_step_<workload>.md.  Keyed by
-# (workload, select_top_k, threshold); other configurations report null.
-MEASURED_TRAFFIC = {
-    ("qwen3_b32", 2, 0.0): {"gate_up": 204335652, "down": 106599894},
-    ("qwen3_b128", 2, 0.0): {"gate_up": 660773920, "down": 350131729},
-    ("mixtral_b64", 2, 0.0): {"gate_up": 1890675817, "down": 1060992118},
-    ("dsv2lite_b64", 2, 0.0): {"gate_up": 579056750, "down": 311375824},
-    ("qwen15_b32", 2, 0.0): {"gate_up": 359498547, "down": 189210759},
-}
+
+def recorded_traffic(workload, S, rho):
+    """HBM bytes per launch (read + write) of the two FFN kernels as recorded from rocprofv3
+    --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/hbm_traffic.json; commands and scale factors in
+    profiles/sere_step_<workload>.md).  The record names the library sources it was taken on;
+    if they have changed since, nothing is reported (null)."""
+    from paper_2602_07616_amd import build as lib_build
+    try:
+        rec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        return {}, "no record"
+    if rec.get("source_hash") != lib_build.source_hash():
+        return {}, "library sources changed since the counters were read (commit %s)" % rec.get("commit")
+    entry = rec.get("entries", {}).get(f"{workload}|{S}|{float(rho)}")
+    if entry is None:
+        return {}, "this configuration was not counted"
+    return entry, "rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE at commit %s" % rec.get("commit")
 
 
 def parse():
@@ -45,11 +59,14 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=384)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="qwen3_b32")
-    ap.add_argument("--S", type=int, default=2, help="select_top_k of the headline SERE step")
+    ap.add_argument("--workload", default=None,
+                    help=f"headline workload (default {HEADLINE}); naming one implies --only-headline")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="skip the other layer shapes of the \"configs\" object")
+    ap.add_argument("--S", type=int, default=0, help="select_top_k of the headline SERE step (0: the workload's first grid setting)")
     ap.add_argument("--rho", type=float, default=0.0, help="threshold of the headline SERE step")
     ap.add_argument("--copies", type=int, default=0, help="weight copies to rotate over (0: auto)")
-    ap.add_argument("--grid", action="store_true", help="also time every (S, rho) of the workload")
+    ap.add_argument("--grid", action="store_true", help="(kept for compatibility: the grid is always timed)")
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep")
     ap.add_argument("--prefill", action="store_true",
                     help="also time prefill-sized batches (512, 1024, 2048 tokens) of the Qwen3-shaped layer")
@@ -107,48 +124,68 @@ class Runner:
             l.set_knobs(S, rho)
 
     def time(self, mode, steps, warmup, hot=False):
-        """-> (mean us/step over exactly `steps` steps, per-replay us/step list, host wall us/step).
-        hot: every step on the same copy of the weights (the last-level cache may serve them).
-        One HIP graph holds GRAPH_STEPS consecutive steps (several passes over the weight
-        copies), as a decoder's graph holds all its layers: a graph launch costs about 12 us
-        on this machine, which a graph of four steps would add as 3 us to every step."""
+        """-> (mean us/step over exactly `steps` steps, per-replay us/step list, host wall us/step,
+        launch label).  hot: every step on the same copy of the weights (the last-level cache may
+        serve them).  One HIP graph holds min(steps, GRAPH_STEPS) consecutive steps, each on the
+        next copy of the weights, as a decoder's graph holds all its layers (a graph launch costs
+        about 12 us on this machine, which a graph of four steps would add as 3 us to every step).
+        Exactly `steps` steps are timed: whole replays of that graph plus, if `steps` is not a
+        multiple, one replay of a second graph holding the remainder.  The per-replay list (for
+        median / p10 / p90) has at least STAT_REPLAYS entries: replays beyond the timed ones are
+        made after the timed region and do not enter the mean."""
         torch = self.torch
         layers = self.layers[:1] * len(self.layers) if hot else self.layers
         n = len(layers)
-        per_graph = n * max(1, GRAPH_STEPS // n) if self.use_graph else n
-        seq = [layers[i % n] for i in range(per_graph)]
+        per_graph = min(steps, GRAPH_STEPS) if self.use_graph else min(steps, n)
+        rounds, rem = divmod(steps, per_graph)
+
+        def capture(count, first):
+            if not self.use_graph or count == 0:
+                return None
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=self.stream):
+                for i in range(count):
+                    self._call(layers[(first + i) % n], mode)
+            for _ in range(3):      # settle: the first replays of a new graph run slower
+                g.replay()
+            return g
+
+        def run(graph, count, first):
+            if graph is not None:
+                graph.replay()
+            else:
+                for i in range(count):
+                    self._call(layers[(first + i) % n], mode)
+
         with torch.cuda.stream(self.stream):
             for i in range(warmup):
                 self._call(layers[i % n], mode)
             self.stream.synchronize()
-            graph = None
-            if self.use_graph:
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph, stream=self.stream):
-                    for l in seq:
-                        self._call(l, mode)
-                graph.replay()
-                self.stream.synchronize()
-            rounds, rem = divmod(steps, per_graph)
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(rounds + 2)]
+            main = capture(per_graph, 0)
+            tail = capture(rem, rounds * per_graph)
+            self.stream.synchronize()
+            extra = max(0, STAT_REPLAYS - rounds)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(rounds + 2 + extra)]
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             ev[0].record(self.stream)
             for r in range(rounds):
-                if graph is not None:
-                    graph.replay()
-                else:
-                    for l in seq:
-                        self._call(l, mode)
+                run(main, per_graph, r * per_graph)
                 ev[r + 1].record(self.stream)
-            for i in range(rem):
-                self._call(layers[i % n], mode)
+            run(tail, rem, rounds * per_graph)
             ev[rounds + 1].record(self.stream)
             torch.cuda.synchronize()
             wall = time.perf_counter() - t0
+            for r in range(extra):
+                run(main, per_graph, 0)
+                ev[rounds + 2 + r].record(self.stream)
+            torch.cuda.synchronize()
         total_ms = ev[0].elapsed_time(ev[rounds + 1])
         per_round = [ev[r].elapsed_time(ev[r + 1]) * 1e3 / per_graph for r in range(rounds)]
-        return total_ms * 1e3 / steps, per_round, wall * 1e6 / steps
+        per_round += [ev[rounds + 1 + r].elapsed_time(ev[rounds + 2 + r]) * 1e3 / per_graph for r in range(extra)]
+        label = (f"hip-graph of {per_graph} steps x {rounds} replays" + (f" + one graph of {rem} steps" if rem else "")
+                 if self.use_graph else "stream")
+        return total_ms * 1e3 / steps, per_round, wall * 1e6 / steps, label
 
     def stage_times(self, mode, steps):
         """Average duration of each kernel stage (HIP events attached to each dispatch on the launch stream)."""
@@ -226,13 +263,106 @@ def cpu_baseline(wl, sim, S, rho, budget_s):
             "mean_us": round(statistics.mean(times) * 1e6, 1)}
 
 
+def measure_config(args, name, S, rho, steps, warmup, headline):
+    """Everything reported for one layer shape: the SERE step at (S, rho), the step without
+    re-routing, the (S, rho) grid of the paper's main tables, the routing-only entry points, the
+    per-kernel durations and the roofline of the dominant kernel."""
+    import numpy as np
+    from paper_2602_07616_amd import workloads as wk
+    spec = wk.SPECS[name]
+    wl = wk.make_workload(spec)
+    eb = spec.elem_bytes
+    expert_bytes = spec.expert_bytes
+    copies = args.copies or max(2, min(16, int(np.ceil(4.0e9 / (spec.experts * expert_bytes)))))
+    run = Runner(wl, None, copies, not args.no_graph)
+    if S <= 0:
+        S, rho = spec.grid[0]
+    quick = min(steps, 200)
+
+    def measure(mode, S_, rho_, steps_, warmup_):
+        run.set_knobs(S_, rho_)
+        nb, na = run.active(mode)
+        us, per_round, wall_us, label = run.time(mode, steps_, warmup_)
+        n_exp = (nb if mode == "baseline" else na) + spec.shared
+        gbs = n_exp * expert_bytes / us * 1e-3
+        pr = sorted(per_round)
+        pct = lambda q: round(pr[min(len(pr) - 1, int(q * len(pr)))], 2) if pr else None
+        at_target = n_exp * expert_bytes / (TARGET_FRAC * HBM_PEAK_GBS) * 1e-3
+        return {"us_per_step": round(us, 2), "median_round_us": round(statistics.median(per_round), 2) if per_round else None,
+                "p10_round_us": pct(0.10), "p90_round_us": pct(0.90), "replays": len(per_round),
+                "host_wall_us": round(wall_us, 2), "active_before": nb, "active_after": na,
+                "experts_read": n_exp, "expert_gb_per_s": round(gbs, 1),
+                "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                "target": {"frac_of_hbm_peak": TARGET_FRAC, "us_per_step_at_target": round(at_target, 2),
+                           "met": bool(gbs / HBM_PEAK_GBS >= TARGET_FRAC), "us_above_target": round(max(0.0, us - at_target), 2)},
+                "launch": label}
+
+    sere = measure("sere", S, rho, steps, warmup)
+    if args.only_sere:
+        return {"sere": sere}, run, wl, S, rho
+    base = measure("baseline", spec.top_k, 0.0, steps, warmup)
+    out = {"tokens": spec.tokens, "hidden": spec.hidden, "experts": spec.experts, "top_k": spec.top_k,
+           "inter": spec.inter, "shared": spec.shared, "dtype": "bf16" if spec.dtype == wk.BF16 else "f32",
+           "select_top_k": S, "threshold": rho, "weight_copies": copies,
+           "sere": sere, "no_reroute": base,
+           "speedup_vs_no_reroute": round(base["us_per_step"] / sere["us_per_step"], 3)}
+    grid = {}
+    for gS, grho in spec.grid:
+        if (gS, grho) == (S, rho):
+            g = sere
+        else:
+            g = measure("sere", gS, grho, quick, min(warmup, 10))
+        grid[f"S={gS},rho={grho}"] = {k: g[k] for k in ("us_per_step", "active_before", "active_after", "experts_read",
+                                                         "expert_gb_per_s", "frac_of_hbm_peak")}
+        grid[f"S={gS},rho={grho}"]["speedup_vs_no_reroute"] = round(base["us_per_step"] / g["us_per_step"], 3)
+    out["grid"] = grid
+    run.set_knobs(S, rho)
+    route_us, _, _, _ = run.time("route", quick, 10)
+    out["route_only_us"] = round(route_us, 2)
+    if headline:
+        hot_us, _, _, _ = run.time("sere", quick, 10, hot=True)
+        for l in run.layers:      # top-K ids for the re-routing-only entry point
+            l.run_route(run.stream)
+        reroute_us, _, _, _ = run.time("reroute", quick, 10)
+        out["reroute_only_us"] = round(reroute_us, 2)
+        out["sere_hot_weights_us"] = round(hot_us, 2)
+
+    # roofline of the dominant kernel: the gate/up projection streams 2/3 of the
+    # surviving experts' bytes
+    run.set_knobs(S, rho)
+    stages = run.stage_times("sere", quick)
+    gateup_bytes = sere["experts_read"] * 2 * spec.hidden * spec.inter * eb
+    down_bytes = sere["experts_read"] * spec.hidden * spec.inter * eb
+    achieved = gateup_bytes / stages["gate_up"] * 1e-3 if stages["gate_up"] else 0.0
+    traffic, traffic_source = recorded_traffic(spec.name, S, rho)
+    roofline = {"bound": "hbm", "kernel": "gate_up", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic.get("gate_up"),
+                "traffic_source": traffic_source,
+                "algorithmic_bytes_per_launch": gateup_bytes,
+                "avg_launch_us": round(stages["gate_up"], 2),
+                "down": {"achieved": round(down_bytes / stages["down"] * 1e-3, 1) if stages["down"] else 0.0,
+                         "frac": round(down_bytes / stages["down"] * 1e-3 / HBM_PEAK_GBS, 4) if stages["down"] else 0.0,
+                         "avg_launch_us": round(stages["down"], 2), "algorithmic_bytes_per_launch": down_bytes,
+                         "traffic": traffic.get("down")},
+                "stage_us": {k: round(v, 2) for k, v in stages.items()}}
+    if headline:
+        # what a plain read of as many bytes of the same weights takes on this machine (context for
+        # `frac`: the published peak is not attainable by any kernel), and a long read
+        read_us, read_bytes = run.plain_read(gateup_bytes)
+        long_us, long_bytes = run.plain_read(spec.experts * 2 * spec.hidden * spec.inter * eb, launches=16)
+        roofline["plain_read"] = {"bytes": read_bytes, "us": round(read_us, 2),
+                                  "gb_per_s": round(read_bytes / read_us * 1e-3, 1),
+                                  "long_read_bytes": long_bytes, "long_read_gb_per_s": round(long_bytes / long_us * 1e-3, 1)}
+    out["roofline"] = roofline
+    return out, run, wl, S, rho
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures ONE GPU: the decode MoE layer runs whole on a single MI355X "
               "(no sharding, no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-    import numpy as np
     import torch
     from paper_2602_07616_amd import binding as B, workloads as wk
     if not torch.cuda.is_available():
@@ -240,29 +370,9 @@ def main():
         sys.exit(2)
     B.load()
 
-    spec = wk.SPECS[args.workload]
-    wl = wk.make_workload(spec)
-    eb = spec.elem_bytes
-    expert_bytes = spec.expert_bytes
-    copies = args.copies or max(2, min(16, int(np.ceil(4.0e9 / (spec.experts * expert_bytes)))))
-    run = Runner(wl, None, copies, not args.no_graph)
-    sim_host = run.sim.cpu().numpy()
-
-    def measure(mode, S, rho, steps, warmup):
-        run.set_knobs(S, rho)
-        nb, na = run.active(mode)
-        us, per_round, wall_us = run.time(mode, steps, warmup)
-        n_exp = (nb if mode == "baseline" else na) + spec.shared
-        gbs = n_exp * expert_bytes / us * 1e-3
-        pr = sorted(per_round)
-        pct = lambda q: round(pr[min(len(pr) - 1, int(q * len(pr)))], 2) if pr else None
-        return {"us_per_step": round(us, 2), "median_round_us": round(statistics.median(per_round), 2) if per_round else None,
-                "p10_round_us": pct(0.10), "p90_round_us": pct(0.90),
-                "host_wall_us": round(wall_us, 2), "active_before": nb, "active_after": na,
-                "experts_read": n_exp, "expert_gb_per_s": round(gbs, 1),
-                "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
-
-    sere = measure("sere", args.S, args.rho, args.steps, args.warmup)
+    name = args.workload or HEADLINE
+    only_headline = args.only_headline or args.workload is not None or args.only_sere
+    head, run, wl, S, rho = measure_config(args, name, args.S, args.rho, args.steps, args.warmup, True)
     if args.only_sere:
         if args.copy_calibration:
             src = torch.ones(128 << 20, dtype=torch.bfloat16, device="cuda")   # 256 MiB
@@ -270,81 +380,68 @@ def main():
             for _ in range(4):
                 dst.copy_(src)
             torch.cuda.synchronize()
-        print(json.dumps({"sere": sere}))
+        print(json.dumps(head))
         return
-    base = measure("baseline", spec.top_k, 0.0, args.steps, args.warmup)
-    run.set_knobs(args.S, args.rho)
-    route_us, _, _ = run.time("route", min(args.steps, 200), 10)
-    hot_us, _, _ = run.time("sere", min(args.steps, 200), 10, hot=True)
-    for l in run.layers:      # top-K ids for the re-routing-only entry point
-        l.run_route(run.stream)
-    reroute_us, _, _ = run.time("reroute", min(args.steps, 200), 10)
-
-    # roofline of the dominant kernel: the gate/up projection streams 2/3 of the
-    # surviving experts' bytes
-    run.set_knobs(args.S, args.rho)
-    stages = run.stage_times("sere", min(args.steps, 200))
-    gateup_bytes = sere["experts_read"] * 2 * spec.hidden * spec.inter * eb
-    down_bytes = sere["experts_read"] * spec.hidden * spec.inter * eb
-    achieved = gateup_bytes / stages["gate_up"] * 1e-3 if stages["gate_up"] else 0.0
-    traffic = MEASURED_TRAFFIC.get((spec.name, args.S, float(args.rho)), {})
-    roofline = {"bound": "hbm", "kernel": "gate_up", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic.get("gate_up"),
-                "algorithmic_bytes_per_launch": gateup_bytes,
-                "avg_launch_us": round(stages["gate_up"], 2),
-                "down": {"achieved": round(down_bytes / stages["down"] * 1e-3, 1) if stages["down"] else 0.0,
-                         "avg_launch_us": round(stages["down"], 2), "algorithmic_bytes_per_launch": down_bytes,
-                         "traffic": traffic.get("down")},
-                "stage_us": {k: round(v, 2) for k, v in stages.items()}}
-    # what a plain read of as many bytes of the same weights takes on this machine (context for
-    # `frac`: the published peak is not attainable by any kernel), and a long read
-    read_us, read_bytes = run.plain_read(gateup_bytes)
-    long_us, long_bytes = run.plain_read(spec.experts * 2 * spec.hidden * spec.inter * eb, launches=16)
-    roofline["plain_read"] = {"bytes": read_bytes, "us": round(read_us, 2),
-                              "gb_per_s": round(read_bytes / read_us * 1e-3, 1),
-                              "long_read_bytes": long_bytes, "long_read_gb_per_s": round(long_bytes / long_us * 1e-3, 1)}
-
+    spec = wl.spec
+    sere, base = head["sere"], head["no_reroute"]
+    sim_host = run.sim.cpu().numpy()
     result = {
         "metric": "us per MoE-layer decode step (SERE) + achieved HBM GB/s, SERE vs no-reroute",
         "value": sere["us_per_step"], "unit": "us/step", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(sere["us_per_step"] * 1e-3, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if spec.dtype == wk.BF16 else "f32", "data": "synthetic",
+        "dtype": head["dtype"], "data": "synthetic",
         "config": {"workload": spec.name, "tokens": spec.tokens, "hidden": spec.hidden,
                    "experts": spec.experts, "top_k": spec.top_k, "inter": spec.inter,
-                   "shared": spec.shared, "select_top_k": args.S, "threshold": args.rho,
-                   "weight_copies": copies, "launch": "stream" if args.no_graph else f"hip-graph of {GRAPH_STEPS} steps",
+                   "shared": spec.shared, "select_top_k": S, "threshold": rho,
+                   "weight_copies": head["weight_copies"], "launch": sere["launch"],
                    "similarity": "Frobenius estimate on the GPU (sere_similarity) from seeded calibration tokens"},
         "sere": sere, "no_reroute": base,
-        "speedup_vs_no_reroute": round(base["us_per_step"] / sere["us_per_step"], 3),
-        "route_only_us": round(route_us, 2),
-        "reroute_only_us": round(reroute_us, 2),
-        "sere_hot_weights_us": round(hot_us, 2),
-        "roofline": roofline,
+        "speedup_vs_no_reroute": head["speedup_vs_no_reroute"],
+        "expert_gb_per_s": sere["expert_gb_per_s"], "frac_of_hbm_peak": sere["frac_of_hbm_peak"],
+        "target": sere["target"],
+        "grid": head["grid"],
+        "route_only_us": head["route_only_us"],
+        "reroute_only_us": head["reroute_only_us"],
+        "sere_hot_weights_us": head["sere_hot_weights_us"],
+        "roofline": head["roofline"],
         "paper_context": "paper: up to 2.0x whole-model decode speedup on NVIDIA H20 under vLLM; "
                          "MoE MLP 227 us and re-routing kernel 6 us per layer-step at batch 32 on H20 "
                          "(not this machine, not the target)",
     }
-
-    if args.grid:
-        result["grid"] = {f"S={S},rho={rho}": measure("sere", S, rho, args.steps, args.warmup)
-                          for S, rho in spec.grid}
     if args.rho_sweep:
-        result["rho_sweep"] = {f"{rho:.1f}": {k: v for k, v in measure("sere", 1, rho, 100, 10).items()
-                                              if k in ("us_per_step", "active_before", "active_after")}
-                               for rho in [i / 10 for i in range(11)]}
+        def quick(rho_):
+            run.set_knobs(1, rho_)
+            nb, na = run.active("sere")
+            us, _, _, _ = run.time("sere", 100, 10)
+            return {"us_per_step": round(us, 2), "active_before": nb, "active_after": na}
+        result["rho_sweep"] = {f"{r:.1f}": quick(r) for r in [i / 10 for i in range(11)]}
+    if args.layers > 0:
+        result["stack"] = stack(args, run, S, rho)
+    del run
+    torch.cuda.empty_cache()
+
+    if not only_headline:
+        configs = {}
+        for other in ALL_WORKLOADS:
+            if other == name:
+                configs[other] = {k: v for k, v in head.items()}
+                continue
+            cfg, r2, _, _, _ = measure_config(args, other, 0, 0.0, args.steps, args.warmup, False)
+            configs[other] = cfg
+            del r2
+            torch.cuda.empty_cache()
+        result["configs"] = configs
     if args.sweep:
         result["sweep"] = sweep(args)
     if args.prefill:
         result["prefill_sized"] = sweep(args, (512, 1024, 2048))
-    if args.layers > 0:
-        result["stack"] = stack(args, run)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, sim_host, args.S, args.rho, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(wl, sim_host, S, rho, args.cpu_seconds)
     print(json.dumps(result))
 
 
-def stack(args, run):
+def stack(args, run, S, rho):
     """L chained layers (layer l reads what layer l-1 wrote; residual added by the
     combine step), one HIP graph per pass; layer l uses weight copy l mod copies,
     so consecutive layers never share cached weights.  Per-layer active counts."""
@@ -353,7 +450,7 @@ def stack(args, run):
     wl, n = run.wl, len(run.layers)
     layers = []
     for l in range(args.layers):
-        layer = device.DeviceLayer.from_workload(wl, run.sim, args.S, args.rho, weights=run.layers[l % n].weights())
+        layer = device.DeviceLayer.from_workload(wl, run.sim, S, rho, weights=run.layers[l % n].weights())
         layer.cfg.flags = B.SERE_FLAG_RESIDUAL
         if layers:
             layer.hidden = layers[-1].out
@@ -405,7 +502,7 @@ def sweep(args, batches=None):
         for label, mode, S in (("no_reroute", "baseline", 8), ("S=2", "sere", 2), ("S=1", "sere", 1)):
             run.set_knobs(S, 0.0)
             nb, na = run.active(mode)
-            us, _, _ = run.time(mode, 200 if T <= 256 else 40, 20 if T <= 256 else 4)
+            us, _, _, _ = run.time(mode, 200 if T <= 256 else 40, 20 if T <= 256 else 4)
             row[label] = {"us_per_step": round(us, 2), "active": nb if mode == "baseline" else na}
         out[str(T)] = row
         del run
