@@ -61,6 +61,14 @@ __device__ __forceinline__ u32x4 upper_from(u32x4 keep, u32x4 other) {
                                        0xF, 0xC, false);
   return r;
 }
+// every lane takes the value of the lane 8 places further round its 16-lane row
+__device__ __forceinline__ u32x4 rotate8(u32x4 v) {
+  u32x4 r;
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+    r[c] = __builtin_amdgcn_update_dpp(0, static_cast<int>(v[c]), 0x128 /*row_ror:8*/, 0xF, 0xF, true);
+  return r;
+}
 // lanes 0-7 of every 16-lane row take `other` from 8 lanes above; lanes 8-15 keep `keep`
 __device__ __forceinline__ u32x4 lower_from(u32x4 keep, u32x4 other) {
   u32x4 r;
@@ -134,7 +142,6 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
                                              unsigned char* lds, f32x4 (&acc)[NA][NT]) {
   using St = Stage<NT, KC>;
   constexpr int KB = KC / 64;          // 64-wide k blocks per chunk
-  constexpr int H0 = (KB + 1) / 2;     // k blocks in the first half of a chunk
   constexpr int NP = LO ? 2 : 1;
   static_assert(NP * 2 * St::kBufBytes <= kStageLdsBytes, "LDS budget");
   const int tid = threadIdx.x, lane = tid & 63;
@@ -178,46 +185,43 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
       for (int j = 0; j < St::kPerThread; ++j)
         *reinterpret_cast<u32x4*>(lds + (buf * NP + pl) * St::kBufBytes + dst0 + kThreadsPerRow * 16 * j) = stage[pl][j];
   };
-  // weights of one half of a chunk: k blocks [b0, b1)
-  u32x4 xa[NA][H0], ya[NA][H0], xb[NA][H0], yb[NA][H0];
-  auto fetch_weights = [&](u32x4 (&x)[NA][H0], u32x4 (&y)[NA][H0], int k0, int b0, int b1) {
+  // Weights: one register slot per 64-wide block of a chunk.  A block's next load (the same
+  // block of the next chunk) is issued right after the block has been multiplied, so that a
+  // wavefront always has a chunk's worth of weight loads in flight, each wait is for the one
+  // oldest load, and nothing is loaded during the last chunk.
+  u32x4 rx[NA][KB], ry[NA][KB];
+  auto load_block = [&](int k0, int b) {
+    const int kk = min(k0 + 64 * b, kend - 64);
 #pragma unroll
-    for (int b = b0; b < b1; ++b) {
-      const int kk = min(k0 + 64 * b, kend - 64);
-#pragma unroll
-      for (int a = 0; a < NA; ++a) {
-        x[a][b - b0] = load_weight(wx[a] + kk);
-        if (!HALF) y[a][b - b0] = load_weight(wy[a] + kk);
-      }
+    for (int a = 0; a < NA; ++a) {
+      rx[a][b] = load_weight(wx[a] + kk);
+      if (!HALF) ry[a][b] = load_weight(wy[a] + kk);
     }
   };
-  auto multiply = [&](const u32x4 (&x)[NA][H0], const u32x4 (&y)[NA][H0], int k0, int b0, int b1, int buf) {
+  auto multiply_block = [&](int k0, int b, int buf) {
+    if (k0 + 64 * b < kend) {  // wave-uniform; a block beyond kend holds a duplicate of the last one
+      u32x4 b_even[NP][NT], b_odd[NP][NT];
 #pragma unroll
-    for (int b = b0; b < b1; ++b) {
-      if (k0 + 64 * b < kend) {  // wave-uniform; a block beyond kend holds a duplicate of the last one
-        u32x4 b_even[NP][NT], b_odd[NP][NT];
+      for (int pl = 0; pl < NP; ++pl)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const unsigned char* at =
+              lds + (buf * NP + pl) * St::kBufBytes + (t * kTile + i) * St::kRowBytes + (64 * b + 16 * g) * 2;
+          b_even[pl][t] = *reinterpret_cast<const u32x4*>(at);
+          b_odd[pl][t] = *reinterpret_cast<const u32x4*>(at + 16);
+        }
+#pragma unroll
+      for (int a = 0; a < NA; ++a) {
+        // HALF: the tile's rows 8-15 are not used; they multiply whatever the lanes hold
+        const u32x4 a_even = HALF ? rx[a][b] : upper_from(rx[a][b], ry[a][b]);
+        const u32x4 a_odd = HALF ? rotate8(rx[a][b]) : lower_from(ry[a][b], rx[a][b]);
 #pragma unroll
         for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
           for (int t = 0; t < NT; ++t) {
-            const unsigned char* at =
-                lds + (buf * NP + pl) * St::kBufBytes + (t * kTile + i) * St::kRowBytes + (64 * b + 16 * g) * 2;
-            b_even[pl][t] = *reinterpret_cast<const u32x4*>(at);
-            b_odd[pl][t] = *reinterpret_cast<const u32x4*>(at + 16);
+            acc[a][t] = mfma_bf16(a_even, b_even[pl][t], acc[a][t]);
+            acc[a][t] = mfma_bf16(a_odd, b_odd[pl][t], acc[a][t]);
           }
-#pragma unroll
-        for (int a = 0; a < NA; ++a) {
-          // HALF: the tile's rows 8-15 are not used; they multiply whatever the lanes hold
-          const u32x4 a_even = HALF ? x[a][b - b0] : upper_from(x[a][b - b0], y[a][b - b0]);
-          const u32x4 a_odd = HALF ? lower_from(x[a][b - b0], x[a][b - b0]) : lower_from(y[a][b - b0], x[a][b - b0]);
-#pragma unroll
-          for (int pl = 0; pl < NP; ++pl)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-              acc[a][t] = mfma_bf16(a_even, b_even[pl][t], acc[a][t]);
-              acc[a][t] = mfma_bf16(a_odd, b_odd[pl][t], acc[a][t]);
-            }
-        }
       }
     }
   };
@@ -225,25 +229,24 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
   if (nch > 0) {
     int k0 = chunk_start(0);
     fetch_tokens(k0);
-    fetch_weights(xa, ya, k0, 0, H0);
-    if (KB > H0) fetch_weights(xb, yb, k0, H0, KB);
+#pragma unroll
+    for (int b = 0; b < KB; ++b) load_block(k0, b);
     store_tokens(0);
     for (int c = 0; c + 1 < nch; ++c) {  // every pass of this loop has a next chunk to fetch
       __syncthreads();  // chunk c is in LDS; nobody still reads the other buffer
       const int k1 = chunk_start(c + 1);
       fetch_tokens(k1);
-      multiply(xa, ya, k0, 0, H0, c & 1);
-      fetch_weights(xa, ya, k1, 0, H0);
-      if (KB > H0) {
-        multiply(xb, yb, k0, H0, KB, c & 1);
-        fetch_weights(xb, yb, k1, H0, KB);
+#pragma unroll
+      for (int b = 0; b < KB; ++b) {
+        multiply_block(k0, b, c & 1);
+        load_block(k1, b);
       }
       store_tokens((c + 1) & 1);
       k0 = k1;
     }
     __syncthreads();
-    multiply(xa, ya, k0, 0, H0, (nch - 1) & 1);
-    if (KB > H0) multiply(xb, yb, k0, H0, KB, (nch - 1) & 1);
+#pragma unroll
+    for (int b = 0; b < KB; ++b) multiply_block(k0, b, (nch - 1) & 1);
   }
   __syncthreads();  // the LDS buffers may be refilled by the caller's next group
 }
