@@ -14,6 +14,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsere.so")
+LIB_FORMAL = os.path.join(HERE, "libsere_formal.so")   # same sources, SERE_FORMAL_HANDOFF=1 (for the tests)
 CLI = os.path.join(HERE, "abi_cli")
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 
@@ -47,20 +48,24 @@ def stale() -> bool:
 def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not stale():
         return LIB
-    tmp = f"{LIB}.{os.getpid()}.tmp"
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-function",
-           *sources(), "-o", tmp]
-    if verbose:
-        print(" ".join(cmd))
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + r.stdout + r.stderr)
-    if verbose:
-        noise = "is not a recognized feature for this target"
-        print("\n".join(ln for ln in r.stderr.splitlines() if noise not in ln))
-    os.replace(tmp, LIB)
+    jobs = []
+    for lib, extra in ((LIB, []), (LIB_FORMAL, ["-DSERE_FORMAL_HANDOFF=1"])):
+        tmp = f"{lib}.{os.getpid()}.tmp"
+        cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Wall", "-Wno-unused-function", *extra,
+               *sources(), "-o", tmp]
+        if verbose:
+            print(" ".join(cmd))
+        jobs.append((lib, tmp, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)))
+    for lib, tmp, proc in jobs:
+        out, err = proc.communicate()
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + out + err)
+        if verbose:
+            noise = "is not a recognized feature for this target"
+            print("\n".join(ln for ln in err.splitlines() if noise not in ln))
+        os.replace(tmp, lib)
     build_cli()
     return LIB
 

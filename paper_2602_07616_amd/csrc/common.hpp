@@ -6,6 +6,22 @@
 
 #include "../../include/sere.h"
 
+// The kernels rest on gfx950 facts (wave64, the 16x16x32 bf16 MFMA and its lane layout, DPP row
+// operations, and the cache behaviour of device-scope stores that the routing kernels' hand-off
+// between workgroups uses): no other target may be built.
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "this library is written for gfx950 (MI355X) only"
+#endif
+
+// 1: the hand-off of top-K ids between workgroups of one launch is ordered by the memory model
+// itself (release on the ticket, acquire by the workgroup that takes the last one, both at device
+// scope).  0 (default): the fence-free hand-off described at topk_route_kernel, which rests on
+// gfx950's behaviour and is several microseconds faster.  Both give the same results; a second
+// copy of the library is built with 1 and the tests compare the two.
+#ifndef SERE_FORMAL_HANDOFF
+#define SERE_FORMAL_HANDOFF 0
+#endif
+
 namespace sere {
 
 constexpr int kWave = 64;

@@ -187,29 +187,41 @@ __global__ __launch_bounds__(256) void router_logits_tokens_kernel(
   for (int q = 0; q < 4; ++q)
 #pragma unroll
     for (int b = 0; b < TB; ++b) acc[q][b] = 0.0;
-  for (int i = lane * 8; i < dh; i += 512) {
-    Raw8<DT> xr[TB], wr[4];
+  // passes of up to four 512-wide chunks, all loads of a pass issued before any arithmetic (the
+  // router weights come cold from HBM on every step: one round trip per pass instead of one per chunk)
+  constexpr int kChunks = TB <= 2 ? 4 : 2;
+  for (int i0 = lane * 8; i0 < dh; i0 += 512 * kChunks) {
+    Raw8<DT> xr[kChunks][TB], wr[kChunks][4];
 #pragma unroll
-    for (int b = 0; b < TB; ++b) xr[b].load(hidden, static_cast<size_t>(min(t0 + b, T - 1)) * dh + i);
+    for (int c = 0; c < kChunks; ++c) {
+      const int i = min(i0 + 512 * c, dh - 8);   // a chunk beyond d_h re-reads the row's end and is not used
 #pragma unroll
-    for (int q = 0; q < 4; ++q) wr[q].load(router_w, static_cast<size_t>(min(e0 + q, M - 1)) * dh + i);
-    double wd[4][8];
+      for (int b = 0; b < TB; ++b) xr[c][b].load(hidden, static_cast<size_t>(min(t0 + b, T - 1)) * dh + i);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float wv[8];
-      wr[q].widen(wv);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) wd[q][j] = static_cast<double>(wv[j]);
+      for (int q = 0; q < 4; ++q) wr[c][q].load(router_w, static_cast<size_t>(min(e0 + q, M - 1)) * dh + i);
     }
 #pragma unroll
-    for (int b = 0; b < TB; ++b) {
-      float xv[8];
-      xr[b].widen(xv);
+    for (int c = 0; c < kChunks; ++c) {
+      if (i0 + 512 * c < dh) {
+        double wd[4][8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const double xd = static_cast<double>(xv[j]);
+        for (int q = 0; q < 4; ++q) {
+          float wv[8];
+          wr[c][q].widen(wv);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) acc[q][b] = fma(xd, wd[q][j], acc[q][b]);
+          for (int j = 0; j < 8; ++j) wd[q][j] = static_cast<double>(wv[j]);
+        }
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+          float xv[8];
+          xr[c][b].widen(xv);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const double xd = static_cast<double>(xv[j]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q][b] = fma(xd, wd[q][j], acc[q][b]);
+          }
+        }
       }
     }
   }
@@ -380,6 +392,7 @@ constexpr int kTopkLoneThreads = 512;    // one workgroup serves the whole batch
                                          // (measured: 1024 threads on one compute unit take 14.5 us, four
                                          // workgroups of 256 take 11.6 us)
 constexpr int kTopkMaxSmallGroups = 64;  // groups of 256 threads up to this many workgroups, of 1024 beyond
+constexpr int kSimPrefetchMaxGroups = 8;  // workgroups of a top-K launch that all prefetch their similarity rows
 constexpr int kRouteWaves = kRouteThreads / kWave;
 constexpr int kItemRows = 32;                     // rows of the sorted slot list per FFN work item (RouteArgs::item_rows may double it)
 constexpr int kIdsInLds = 4096;                   // slots whose ids a lone workgroup keeps in LDS
@@ -413,7 +426,7 @@ struct SimPrefetch {
   float v[PR * NC];
 };
 template <int NC>
-__device__ __forceinline__ void prefetch_sim(const RouteArgs& p, SimPrefetch<NC>& pf) {
+__device__ __forceinline__ void prefetch_sim(const RouteArgs& p, SimPrefetch<NC>& pf, bool enabled = true) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int q = lane >> 4, i = lane & 15;
 #pragma unroll
@@ -421,7 +434,7 @@ __device__ __forceinline__ void prefetch_sim(const RouteArgs& p, SimPrefetch<NC>
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       const int u = 4 * wave + q + 64 * r, v = i + 16 * c;
-      pf.v[r * NC + c] = (p.reroute && u < p.M && v < p.M) ? p.sim[static_cast<size_t>(u) * p.M + v] : 0.0f;
+      pf.v[r * NC + c] = (enabled && p.reroute && u < p.M && v < p.M) ? p.sim[static_cast<size_t>(u) * p.M + v] : 0.0f;
     }
   }
 }
@@ -438,7 +451,8 @@ __device__ __forceinline__ void simmax_step(float& sv, int& iv) {
 }
 
 template <bool IDS_IN_LDS, int NC>
-__device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, const SimPrefetch<NC>& pf) {
+__device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, const SimPrefetch<NC>& pf,
+                                            bool prefetched = true) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int M = p.M, K = p.K, S = p.S;
   const int A = p.T * K;
@@ -487,7 +501,7 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
         const int v = i + 16 * c;
         if (v < M) {
           float sv;
-          if (r < SimPrefetch<NC>::PR)
+          if (r < SimPrefetch<NC>::PR && prefetched)   // prefetched: uniform over the workgroup
             sv = pf.v[(r < SimPrefetch<NC>::PR ? r : 0) * NC + c];
           else
             sv = sec ? p.sim[static_cast<size_t>(u) * M + v] : 0.0f;
@@ -663,8 +677,12 @@ __global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const uint64_
   // or 256 -- one wavefront per SIMD, the merge being bound by the vector ALU -- so that a batch
   // shared by several workgroups spreads over more compute units)
   const int group_tokens = p.topk_threads / LP;
+  // The similarity rows are requested before the top-K so that their latency hides behind it.
+  // Only the workgroup that runs the batch-wide step uses them, and which one that is is not
+  // known yet: with a handful of workgroups every one of them asks (the lines come from L2), with
+  // many the step is long anyway and the rows are loaded where they are needed instead.
   SimPrefetch<NC> pf;
-  prefetch_sim(p, pf);
+  prefetch_sim(p, pf, gridDim.x <= kSimPrefetchMaxGroups);
   const int nlists = (p.M + 15) >> 4;
   const int t = blockIdx.x * group_tokens + threadIdx.x / LP;
   const bool lone = gridDim.x == 1 && p.T * p.K <= kIdsInLds;
@@ -682,22 +700,45 @@ __global__ __launch_bounds__(kRouteThreads) void topk_route_kernel(const uint64_
     return;
   }
   if (gridDim.x > 1) {
-    // The ids were stored at device scope (written through): once those stores have been
-    // acknowledged they are visible to every workgroup, with no cache write-back or invalidation
-    // (a device-scope fence costs this kernel several microseconds on this multi-die part).  The
-    // workgroup then takes its ticket; the one that takes the last ticket has, through the order of
-    // the tickets, every other workgroup's acknowledged stores before it, and reads the ids with
-    // device-scope loads.
+#if SERE_FORMAL_HANDOFF
+    // Ordered by the memory model: the barrier orders every thread's id stores before thread 0's
+    // ticket, the ticket is a device-scope release (this workgroup's stores become visible) and
+    // acquire (the last taker sees every earlier taker's), the second barrier hands that on to
+    // the other threads.  On this multi-die part the release writes the L2 back and the acquire
+    // invalidates it, which is what the default path avoids.
+    __syncthreads();
+    if (threadIdx.x == 0)
+      s.flag = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == static_cast<int>(gridDim.x) - 1;
+    __syncthreads();
+    if (!s.flag) return;
+#else
+    // Fence-free hand-off.  What it rests on (gfx950, not the HIP memory model):
+    //  - the ids were written with device-scope atomic stores, which the compiler emits as
+    //    global stores with the sc1 bit: they write through this die's L2 to memory instead of
+    //    staying dirty in it, and no compiler transformation may drop or merge them;
+    //  - s_waitcnt vmcnt(0) (s_waitcnt(0) below waits on every counter) returns only after those
+    //    stores have been acknowledged, i.e. have reached the point of coherence; gfx950 counts
+    //    stores in vmcnt like loads (there is no separate store counter), and the builtin is a
+    //    scheduling barrier for memory operations;
+    //  - the ticket is a device-scope atomic add, performed at the point of coherence, so the
+    //    workgroup that reads gridDim.x - 1 runs after every other workgroup's acknowledgement;
+    //  - that workgroup reads the ids with device-scope atomic loads (sc1: they bypass its own
+    //    die's L2, which may hold stale lines), and ONLY the ids: route_phase<false> must not
+    //    read any other data written by this launch's other workgroups (it does not: the gate
+    //    weights, for one, are never read back).
+    // Two device-scope fences here cost this kernel several microseconds (an L2 write-back and
+    // an invalidate on a part with one L2 per die).
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (threadIdx.x == 0)
       s.flag = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == static_cast<int>(gridDim.x) - 1;
     __syncthreads();
     if (!s.flag) return;
+#endif
   } else {
     __syncthreads();
   }
-  route_phase<false>(p, s, pf);
+  route_phase<false>(p, s, pf, gridDim.x <= kSimPrefetchMaxGroups);
 }
 
 }  // namespace sere

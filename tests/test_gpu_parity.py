@@ -618,6 +618,36 @@ def test_many_runs_of_the_shared_topk_are_bit_identical(dev, tokens):
             assert (layer.out == first_out).all(), rep
 
 
+@pytest.mark.parametrize("tokens", [128, 300, 2048])
+def test_formally_ordered_handoff_gives_the_same_routing(dev, tokens):
+    """The library is also built with SERE_FORMAL_HANDOFF=1 (top-K ids handed between workgroups
+    under a device-scope release/acquire on the ticket instead of the fence-free path): both
+    builds must give the oracle's integers on batches whose top-K is shared by 4, 10 and 16
+    workgroups (with more than 8 the similarity rows are no longer prefetched by every one)."""
+    import ctypes
+    import torch
+    from paper_2602_07616_amd import binding as B, build as lib_build
+    formal = ctypes.CDLL(lib_build.LIB_FORMAL)
+    vp = ctypes.c_void_p
+    formal.sere_route.restype = ctypes.c_int
+    formal.sere_route.argtypes = [ctypes.POINTER(B.sere_config), vp, vp, vp, ctypes.POINTER(B.sere_route_out), vp,
+                                  ctypes.c_size_t, vp]
+    wl, layer, sim = device_layer(dev, "qwen3_b128", None if tokens == 128 else tokens)
+    for S, rho in ((2, 0.0), (1, 0.5)):
+        layer.set_knobs(S, rho)
+        ref = oracle_route(wl, sim, S, rho, ("sweep", tokens))
+        layer.run_route()
+        check_routing(layer.routing_to_host(), ref, layer.cfg)
+        for name, _ in B.sere_route_out._fields_:
+            getattr(layer.route, name).fill_(-7)
+        out = layer.route.as_struct()
+        st = formal.sere_route(ctypes.byref(layer.cfg), layer.hidden.data_ptr(), layer.router_w.data_ptr(),
+                               layer.sim.data_ptr(), ctypes.byref(out), layer.workspace.data_ptr(),
+                               layer.workspace.numel(), torch.cuda.current_stream().cuda_stream)
+        assert st == B.SERE_OK
+        check_routing(layer.routing_to_host(), ref, layer.cfg)
+
+
 def test_stage_timing_reports_every_stage(dev):
     from paper_2602_07616_amd import binding as B
     wl, layer, sim = device_layer(dev, "tiny")
