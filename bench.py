@@ -202,6 +202,28 @@ class Runner:
             B.sere_stage_timing(False)
         return {s: (ms[s] * 1e3 / cnt[s] if cnt[s] else 0.0) for s in ms}
 
+    def similarity_timing(self):
+        """The set-up step (sere_similarity, Frobenius metric) once more with per-kernel events: us per
+        calibration batch of the experts' forward pass and of the pair stage (Gram matrix of the
+        experts' outputs on the fp64 matrix cores, distances, accumulation), and the pair stage's
+        share of the fp64 MFMA peak: 2 * (upper-triangular 32 x 32 blocks) * n * d_h flop per batch."""
+        from paper_2602_07616_amd import binding as B, device
+        sp = self.wl.spec
+        batches, n = self.wl.calib.shape[0], self.wl.calib.shape[1]
+        B.sere_stage_timing(True)
+        device.similarity_on_device(self.wl, self.layers[0].weights())
+        ms, cnt = B.sere_stage_timing_read()
+        B.sere_stage_timing(False)
+        nb = (sp.experts + 31) // 32
+        flop = 2.0 * (nb * (nb + 1) // 2) * 32 * 32 * n * sp.hidden
+        pair_us = ms["sim_pairs"] * 1e3 / batches
+        return {"calibration_batches": batches, "tokens_per_batch": n,
+                "forward_us_per_batch": round((ms["gate_up"] + ms["down"]) * 1e3 / batches, 2),
+                "pair_stage_us_per_batch": round(pair_us, 2),
+                "pair_stage_roofline": {"bound": "mfma", "dtype": "f64", "achieved": round(flop / pair_us * 1e-6, 2),
+                                        "peak": 78.6, "unit": "TFLOP/s", "frac": round(flop / pair_us * 1e-6 / 78.6, 4),
+                                        "flop_per_batch": flop}}
+
     def plain_read(self, nbytes, launches=64):
         """What the memory system delivers for a plain read of `nbytes` of this workload's own weight
         bytes (library helper sere_stream_read): us per launch over back-to-back launches that each
@@ -326,6 +348,7 @@ def measure_config(args, name, S, rho, steps, warmup, headline):
         reroute_us, _, _, _ = run.time("reroute", quick, 10)
         out["reroute_only_us"] = round(reroute_us, 2)
         out["sere_hot_weights_us"] = round(hot_us, 2)
+        out["similarity_setup"] = run.similarity_timing()
 
     # roofline of the dominant kernel: the gate/up projection streams 2/3 of the
     # surviving experts' bytes
@@ -404,6 +427,7 @@ def main():
         "route_only_us": head["route_only_us"],
         "reroute_only_us": head["reroute_only_us"],
         "sere_hot_weights_us": head["sere_hot_weights_us"],
+        "similarity_setup": head["similarity_setup"],
         "roofline": head["roofline"],
         "paper_context": "paper: up to 2.0x whole-model decode speedup on NVIDIA H20 under vLLM; "
                          "MoE MLP 227 us and re-routing kernel 6 us per layer-step at batch 32 on H20 "

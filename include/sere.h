@@ -228,7 +228,11 @@ int sere_moe_decode_static(const sere_config *cfg, const void *hidden, const voi
  * Similarity"; appendix algorithm "Expert Similarity Estimation"): for each of
  * `num_batches` batches of `batch_tokens` tokens every routed expert is run on
  * every token, x_pq = ||A_p - A_q||_F, Sim(p,q) = 1 - x_pq / max over all pairs
- * of that batch, and sim = the mean of Sim over the batches (diagonal 1).
+ * of that batch, and sim = the mean of Sim over the batches (diagonal 1).  The
+ * distances come from the Gram matrix of the experts' flattened outputs,
+ * x_pq^2 = <A_p,A_p> + <A_q,A_q> - 2 <A_p,A_q>, formed in fp64 on the matrix
+ * cores; pairs whose squared distance is below 1e-9 of <A_p,A_p> + <A_q,A_q>
+ * (near-identical experts) are recomputed as a direct difference.
  * With SERE_FLAG_SIM_COSINE in cfg->flags the metric is the cosine one of the
  * appendix "Cosine Similarity" instead: Sim(p,q) = the mean over the batch's
  * tokens of the cosine between the two experts' outputs for that token (a
@@ -298,7 +302,9 @@ int sere_similarity_cka(const sere_config *cfg, const void *calib, int32_t num_b
 #define SERE_STAGE_GATE_UP 2  /* gate/up projections + SiLU * up         */
 #define SERE_STAGE_DOWN 3     /* down projection                         */
 #define SERE_STAGE_COMBINE 4  /* weighted sum over slots, output store   */
-#define SERE_NUM_STAGES 5
+#define SERE_STAGE_SIM_PAIRS 5 /* sere_similarity*: everything after the experts' forward pass
+                                  (Gram matrices, pairwise metric, accumulation)              */
+#define SERE_NUM_STAGES 6
 #define SERE_TIMING_MAX_RECORDS 8192
 int sere_stage_timing(int enable);
 int sere_stage_timing_read(double *total_ms, int32_t *launches);

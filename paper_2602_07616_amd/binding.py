@@ -32,7 +32,7 @@ SERE_ERR_SCRATCH_TOO_SMALL = -11
 SERE_STATIC_SCRATCH_BYTES = 32 << 20
 SERE_CKA_LINEAR, SERE_CKA_RBF, SERE_CKA_POLY = 0, 1, 2
 
-STAGES = ("router", "route", "gate_up", "down", "combine")
+STAGES = ("router", "route", "gate_up", "down", "combine", "sim_pairs")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsere.so")

@@ -3,6 +3,7 @@
 #include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -467,8 +468,11 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
 
 // ------------------------------------------------------------- similarity ---
 struct SimLayout {
-  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, gram, rowsum, diag, total;
+  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, gram, rowsum, diag, gram_part, twins,
+      total;
   int rows, ksplit;
+  int gram_splits;      // Frobenius metric: slices of the flattened outputs in the Gram kernel
+  long long gram_chunk; // ... and their length
 };
 
 static SimLayout make_sim_layout(const sere_config& c, int n) {
@@ -495,6 +499,15 @@ static SimLayout make_sim_layout(const sere_config& c, int n) {
     l.gram = take(R * n * sizeof(double));
     l.rowsum = take(R * sizeof(double));
     l.diag = take(R * sizeof(double));
+  }
+  if ((c.flags & (SERE_FLAG_SIM_CKA_LINEAR | SERE_FLAG_SIM_COSINE)) == 0) {  // Frobenius: partial Gram matrices of the experts
+    const long long L = static_cast<long long>(n) * c.hidden;
+    long long chunk = (L + kGramMaxSplits - 1) / kGramMaxSplits;
+    chunk = std::max<long long>(256, (chunk + 15) / 16 * 16);
+    l.gram_chunk = chunk;
+    l.gram_splits = static_cast<int>((L + chunk - 1) / chunk);
+    l.gram_part = take(static_cast<size_t>(l.gram_splits) * M * M * sizeof(double));
+    l.twins = take((1 + 2 * M * M) * sizeof(int32_t));
   }
   l.total = o;
   return l;
@@ -578,11 +591,20 @@ static int similarity(const sere_config* cfg, const void* calib, int32_t num_bat
       }
       hipLaunchKernelGGL(pair_hsic_kernel, dim3(M, M), dim3(256), 0, s, gram, rowsum, n, M, dist);
     } else {
-      hipLaunchKernelGGL(pair_distance_kernel, dim3(M, M), dim3(256), 0, s, f.y, l.ksplit, l.rows, n, cfg->hidden,
-                         M, dist);
+      double* part = reinterpret_cast<double*>(ws + l.gram_part);
+      int32_t* twins = reinterpret_cast<int32_t*>(ws + l.twins);
+      const int nb = (M + kGramBlock - 1) / kGramBlock;
+      launch_stage(SERE_STAGE_SIM_PAIRS, s, clear_word_kernel, dim3(1), dim3(64), twins);
+      launch_stage(SERE_STAGE_SIM_PAIRS, s, frobenius_gram_kernel, dim3(nb * (nb + 1) / 2, l.gram_splits), dim3(256), f.y,
+                   l.ksplit, l.rows, n, cfg->hidden, M, l.gram_chunk, part);
+      launch_stage(SERE_STAGE_SIM_PAIRS, s, frobenius_from_gram_kernel, dim3((M * M + 255) / 256), dim3(256), part,
+                   l.gram_splits, M, dist, twins);
+      launch_stage(SERE_STAGE_SIM_PAIRS, s, pair_distance_kernel, dim3(256), dim3(256), f.y, l.ksplit, l.rows, n,
+                   cfg->hidden, M, static_cast<const int32_t*>(twins), dist);
     }
-    hipLaunchKernelGGL(similarity_accumulate_kernel, dim3(1), dim3(1024), 0, s, dist, M, b, num_batches, metric,
-                       reinterpret_cast<double*>(ws + l.acc), sim);
+    launch_stage(SERE_STAGE_SIM_PAIRS, s, similarity_accumulate_kernel, dim3(1), dim3(1024),
+                 static_cast<const double*>(dist), M, b, static_cast<int>(num_batches), metric,
+                 reinterpret_cast<double*>(ws + l.acc), sim);
   }
   return hip_status();
 }

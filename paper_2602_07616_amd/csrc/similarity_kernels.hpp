@@ -30,18 +30,126 @@ __global__ __launch_bounds__(256) void similarity_worklist_kernel(int M, int n, 
   }
 }
 
-// dist[p][q] = sqrt(sum_i (A_p[i] - A_q[i])^2), A_e = sum over slices of y[slice][e*n .. e*n+n) rows.
-// grid (M, M), 256 threads; fp64 accumulation.
+// a fill kernel for one counter word (usable under graph capture, where a memset node is not)
+__global__ void clear_word_kernel(int32_t* word) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *word = 0;
+}
+
+// Frobenius distances of all pairs (appendix "Frobenius Similarity"), x_pq = ||A_p - A_q||_F, from
+// the Gram matrix of the experts' outputs: with V_e the output of expert e on the batch, flattened
+// to one vector of L = n * d_h numbers (A_e = sum over slices of y[slice][e*n .. e*n+n) rows),
+//   x_pq^2 = <V_p, V_p> + <V_q, V_q> - 2 <V_p, V_q>.
+// The Gram matrix is a dense contraction over L and runs on the matrix cores in fp64
+// (v_mfma_f64_16x16x4: products of fp32 numbers are exact in fp64, sums carry ~1e-16 relative
+// rounding each), so the cancellation in the formula above costs at most ~1e-15 of an output's
+// squared norm: harmless for every pair but near-identical twins, which are recomputed as a
+// direct difference (pair_distance_kernel on a list of flagged pairs).
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+constexpr int kGramBlock = 32;     // experts per side of a workgroup's block (2 x 2 tiles of 16 x 16, one per wavefront)
+constexpr int kGramMaxSplits = 64; // slices of L, so that M = 128 gives 10 x 64 workgroups
+constexpr double kGramTwinThreshold = 1e-9;  // x_pq^2 below this fraction of <V_p,V_p> + <V_q,V_q>: recompute directly
+
+// upper-triangular blocks (bp <= bq) numbered row by row
+__device__ __forceinline__ void gram_block_of(int index, int nb, int& bp, int& bq) {
+  bp = 0;
+  while (index >= nb - bp) {
+    index -= nb - bp;
+    ++bp;
+  }
+  bq = bp + index;
+}
+
+// part[split][p][q] = sum over the split's range of L of V_p[k] * V_q[k], for every (p, q) of the
+// upper-triangular 32 x 32 blocks.  grid (nb (nb + 1) / 2, nsplit), 256 threads; lane l of a
+// wavefront holds row l % 16 of its tile, and of every 16 consecutive k the four l / 16 ... (the
+// order of k inside the sum is free as long as both operands agree).
+__global__ __launch_bounds__(256) void frobenius_gram_kernel(const float* __restrict__ y, int ksplit, int rows, int n,
+                                                             int dh, int M, long long chunk,
+                                                             double* __restrict__ part) {
+  const int nb = (M + kGramBlock - 1) / kGramBlock;
+  int bp, bq;
+  gram_block_of(blockIdx.x, nb, bp, bq);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r16 = lane & 15, kq = lane >> 4;
+  const int p0 = bp * kGramBlock + (wave >> 1) * 16, q0 = bq * kGramBlock + (wave & 1) * 16;
+  const long long L = static_cast<long long>(n) * dh;             // multiple of 64
+  const size_t slice = static_cast<size_t>(rows) * dh;
+  const float* ap = y + static_cast<size_t>(min(p0 + r16, M - 1)) * L + 4 * kq;   // rows beyond M repeat the last one (unused)
+  const float* aq = y + static_cast<size_t>(min(q0 + r16, M - 1)) * L + 4 * kq;
+  const long long kbeg = blockIdx.y * chunk, kend = min(kbeg + chunk, L);       // chunk: multiple of 16
+  f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+  for (long long k = kbeg; k < kend; k += 16) {
+    float4 a = *reinterpret_cast<const float4*>(ap + k), b = *reinterpret_cast<const float4*>(aq + k);
+    for (int s = 1; s < ksplit; ++s) {
+      const float4 a2 = *reinterpret_cast<const float4*>(ap + s * slice + k);
+      const float4 b2 = *reinterpret_cast<const float4*>(aq + s * slice + k);
+      a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+      b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
+    }
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(a.x), static_cast<double>(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(a.y), static_cast<double>(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(a.z), static_cast<double>(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(a.w), static_cast<double>(b.w), acc, 0, 0, 0);
+  }
+  // lane l holds D[l / 16 + 4 r][l % 16], r = 0..3 (the fp64 tile interleaves its row blocks)
+  double* out = part + static_cast<size_t>(blockIdx.y) * M * M;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int pp = p0 + kq + 4 * r, qq = q0 + r16;
+    if (pp < M && qq < M) out[static_cast<size_t>(pp) * M + qq] = acc[r];
+  }
+}
+
+// dist[p][q] = sqrt(G_pp + G_qq - 2 G_pq) with G = the sum of the partial Gram matrices in fixed
+// order (entries below the block diagonal are read from their mirror image).  A pair whose squared
+// distance is below kGramTwinThreshold of G_pp + G_qq (near-identical outputs: the subtraction has
+// cancelled most digits) is put on the `twins` list instead: twins[0] = count, then (p, q) pairs;
+// its dist entry is filled by pair_distance_kernel.  *twins must be 0 at launch.
+// grid ceil(M * M / 256), 256 threads.
+__global__ __launch_bounds__(256) void frobenius_from_gram_kernel(const double* __restrict__ part, int nsplit, int M,
+                                                                  double* __restrict__ dist, int32_t* twins) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= M * M) return;
+  const int p = idx / M, q = idx % M;
+  auto gram = [&](int a, int b) {
+    if (a / kGramBlock > b / kGramBlock) {
+      const int t = a;
+      a = b;
+      b = t;
+    }
+    double g = 0.0;
+    for (int s = 0; s < nsplit; ++s) g += part[(static_cast<size_t>(s) * M + a) * M + b];
+    return g;
+  };
+  double d = 0.0;
+  if (p != q) {
+    const double gpp = gram(p, p), gqq = gram(q, q), gpq = gram(p, q);
+    const double d2 = (gpp + gqq) - 2.0 * gpq;
+    if (d2 < kGramTwinThreshold * (gpp + gqq)) {
+      const int at = atomicAdd(twins, 1);
+      twins[1 + 2 * at] = p;
+      twins[2 + 2 * at] = q;
+    } else {
+      d = sqrt(d2);
+    }
+  }
+  dist[idx] = d;
+}
+
+// dist[p][q] = sqrt(sum_i (A_p[i] - A_q[i])^2) as a direct difference, for the pairs on the twins
+// list.  grid: any number of workgroups (they stride over the list), 256 threads; fp64 accumulation.
 __global__ __launch_bounds__(256) void pair_distance_kernel(const float* __restrict__ y, int ksplit, int rows,
-                                                            int n, int dh, int M, double* __restrict__ dist) {
+                                                            int n, int dh, int M, const int32_t* __restrict__ twins,
+                                                            double* __restrict__ dist) {
   __shared__ double part[4];
-  const int p = blockIdx.y, q = blockIdx.x;
+  const int count = twins[0];
   const size_t len = static_cast<size_t>(n) * dh;          // multiple of 64
   const size_t slice = static_cast<size_t>(rows) * dh;
-  const float* ap = y + static_cast<size_t>(p) * len;
-  const float* aq = y + static_cast<size_t>(q) * len;
-  double acc = 0.0;
-  if (p != q) {
+  for (int t = blockIdx.x; t < count; t += gridDim.x) {
+    const int p = twins[1 + 2 * t], q = twins[2 + 2 * t];
+    const float* ap = y + static_cast<size_t>(p) * len;
+    const float* aq = y + static_cast<size_t>(q) * len;
+    double acc = 0.0;
     for (size_t i = static_cast<size_t>(threadIdx.x) * 4; i < len; i += 1024) {
       float4 a = *reinterpret_cast<const float4*>(ap + i), b = *reinterpret_cast<const float4*>(aq + i);
       for (int s = 1; s < ksplit; ++s) {
@@ -54,11 +162,12 @@ __global__ __launch_bounds__(256) void pair_distance_kernel(const float* __restr
       const double dz = static_cast<double>(a.z) - b.z, dw = static_cast<double>(a.w) - b.w;
       acc += dx * dx + dy * dy + dz * dz + dw * dw;
     }
+    acc = wave_sum(acc);
+    __syncthreads();   // part[] of the previous pair has been read
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) dist[static_cast<size_t>(p) * M + q] = sqrt((part[0] + part[1]) + (part[2] + part[3]));
   }
-  acc = wave_sum(acc);
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) dist[static_cast<size_t>(p) * M + q] = sqrt((part[0] + part[1]) + (part[2] + part[3]));
 }
 
 // Cosine metric (appendix "Cosine Similarity"): out[p][q] = (1/n) sum over tokens i of

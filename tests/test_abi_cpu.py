@@ -161,7 +161,9 @@ def test_cka_similarity_batch_size_limits():
         assert lib.sere_similarity(ctypes.byref(cfg), FAKE, 1, n, FAKE, FAKE, FAKE, FAKE, 1 << 40,
                                    None) == B.SERE_ERR_BAD_SHAPE
     plain = good()
+    plain.flags = B.SERE_FLAG_SIM_COSINE      # the metric with no buffers of its own
     assert B.sere_similarity_workspace_bytes(cfg, 64) > B.sere_similarity_workspace_bytes(plain, 64) > 0
+    assert B.sere_similarity_workspace_bytes(good(), 64) > B.sere_similarity_workspace_bytes(plain, 64)   # partial Gram matrices
     assert lib.sere_similarity(ctypes.byref(cfg), FAKE, 1, 64, FAKE, FAKE, FAKE, FAKE, 0,
                                None) == B.SERE_ERR_WORKSPACE_TOO_SMALL
 
@@ -215,7 +217,7 @@ def test_cka_kernel_parameters_validated():
     for kernel, p0, p1 in ((B.SERE_CKA_LINEAR, 0.0, 0.0), (B.SERE_CKA_RBF, 0.5, 0.0), (B.SERE_CKA_POLY, -1.0, 3.0)):
         assert call(kernel, p0, p1) == B.SERE_ERR_WORKSPACE_TOO_SMALL      # accepted up to the workspace check
         assert call(kernel, p0, p1, n=3) == B.SERE_ERR_BAD_SHAPE
-    assert B.sere_similarity_cka_workspace_bytes(cfg, 64) > B.sere_similarity_workspace_bytes(cfg, 64)
     cfg.flags = B.SERE_FLAG_SIM_COSINE
+    assert B.sere_similarity_cka_workspace_bytes(cfg, 64) > B.sere_similarity_workspace_bytes(cfg, 64)
     assert call(B.SERE_CKA_RBF, 0.5, 0.0) == B.SERE_ERR_WORKSPACE_TOO_SMALL
     assert lib.sere_similarity_cka(None, FAKE, 1, 64, FAKE, FAKE, 0, 0.0, 0.0, FAKE, FAKE, 0, None) == B.SERE_ERR_NULL_PTR

@@ -657,8 +657,18 @@ def test_stage_timing_reports_every_stage(dev):
         layer.run_decode(with_outputs=False)
     ms, n = B.sere_stage_timing_read()
     B.sere_stage_timing(False)
-    assert all(n[s] == 3 for s in B.STAGES), n
-    assert all(ms[s] > 0 for s in B.STAGES), ms
+    decode_stages = [s for s in B.STAGES if s != "sim_pairs"]
+    assert all(n[s] == 3 for s in decode_stages), n
+    assert all(ms[s] > 0 for s in decode_stages), ms
+    assert n["sim_pairs"] == 0
+    # the similarity estimation reports its own stage next to the experts' forward pass
+    B.sere_stage_timing(True)
+    dev.similarity_on_device(wl, layer.weights())
+    ms, n = B.sere_stage_timing_read()
+    B.sere_stage_timing(False)
+    batches = wl.calib.shape[0]
+    assert n["gate_up"] == batches and n["down"] == batches and n["sim_pairs"] == 5 * batches, n
+    assert ms["sim_pairs"] > 0
 
 
 # ------------------------------------------------------- similarity matrix ---
@@ -682,6 +692,24 @@ def test_similarity_parity(dev, name):
         a, b = sp.twin_src + i, sp.twin_dst + i
         row = got[a].copy(); row[a] = -1
         assert int(np.argmax(row)) == b
+
+
+@pytest.mark.parametrize("dtype", [wk.F32, wk.BF16])
+def test_similarity_of_exact_twins_takes_the_direct_path(dev, dtype):
+    """Experts 6-11 are bit-identical copies of experts 0-5 (noise 0): their Gram-matrix distance
+    cancels completely, so these pairs go through the direct-difference fallback and come out as
+    exactly 0 (similarity 1); odd expert count and 40 tokens per batch (partial 32-blocks)."""
+    spec = wk.custom_spec("twins0", dtype, 256, 13, 2, 192, 0, 4, 6400 + dtype, twin_src=0, twin_dst=6, twin_n=6,
+                          twin_noise=0.0, calib_batches=2, calib_tokens=40)
+    wl = wk.make_workload(spec)
+    assert np.array_equal(wl.w_gate_up[0], wl.w_gate_up[6]) and np.array_equal(wl.w_down[5], wl.w_down[11])
+    got = dev.similarity_on_device(wl).cpu().numpy()
+    want = oracle.similarity_frobenius(wl.calib, wl.w_gate_up, wl.w_down, dtype)
+    tol = 1e-5 if dtype == wk.F32 else 5e-3
+    assert np.abs(got - want).max() <= tol, np.abs(got - want).max()
+    for i in range(6):
+        assert got[i, 6 + i] == 1.0 and got[6 + i, i] == 1.0 and want[i, 6 + i] == 1.0
+    assert np.array_equal(got, got.T)
 
 
 @pytest.mark.parametrize("name", ["tiny", "qwen15_b32"])
