@@ -206,7 +206,7 @@ class Runner:
         """The set-up step (sere_similarity, Frobenius metric) once more with per-kernel events: us per
         calibration batch of the experts' forward pass and of the pair stage (Gram matrix of the
         experts' outputs on the fp64 matrix cores, distances, accumulation), and the pair stage's
-        share of the fp64 MFMA peak: 2 * (upper-triangular 32 x 32 blocks) * n * d_h flop per batch."""
+        share of the fp64 MFMA peak: 2 * (upper-triangular 64 x 64 blocks) * n * d_h flop per batch."""
         from paper_2602_07616_amd import binding as B, device
         sp = self.wl.spec
         batches, n = self.wl.calib.shape[0], self.wl.calib.shape[1]
@@ -214,8 +214,8 @@ class Runner:
         device.similarity_on_device(self.wl, self.layers[0].weights())
         ms, cnt = B.sere_stage_timing_read()
         B.sere_stage_timing(False)
-        nb = (sp.experts + 31) // 32
-        flop = 2.0 * (nb * (nb + 1) // 2) * 32 * 32 * n * sp.hidden
+        nb = (sp.experts + 63) // 64
+        flop = 2.0 * (nb * (nb + 1) // 2) * 64 * 64 * n * sp.hidden
         pair_us = ms["sim_pairs"] * 1e3 / batches
         return {"calibration_batches": batches, "tokens_per_batch": n,
                 "forward_us_per_batch": round((ms["gate_up"] + ms["down"]) * 1e3 / batches, 2),
@@ -466,38 +466,30 @@ def main():
 
 
 def stack(args, run, S, rho):
-    """L chained layers (layer l reads what layer l-1 wrote; residual added by the
-    combine step), one HIP graph per pass; layer l uses weight copy l mod copies,
-    so consecutive layers never share cached weights.  Per-layer active counts."""
+    """L chained layers (layer l reads what layer l-1 wrote; the residual is added by the combine
+    step), one HIP graph per pass.  Every layer has its own weights (independent seeds) and its own
+    similarity matrix, estimated on the GPU from that layer's weights (Sec. 3.1.1 defines one
+    matrix per layer).  Per-layer active counts."""
     import torch
-    from paper_2602_07616_amd import binding as B, device
-    wl, n = run.wl, len(run.layers)
-    layers = []
-    for l in range(args.layers):
-        layer = device.DeviceLayer.from_workload(wl, run.sim, S, rho, weights=run.layers[l % n].weights())
-        layer.cfg.flags = B.SERE_FLAG_RESIDUAL
-        if layers:
-            layer.hidden = layers[-1].out
-        layers.append(layer)
+    from paper_2602_07616_amd import device, workloads as wk
+    specs = wk.stack_specs(run.wl.spec, args.layers)
+    wls = [wk.make_workload(sp) for sp in specs]
+    sims = [device.similarity_on_device(w) for w in wls]
+    stk = device.DecodeStack(wls, sims, S, rho)
+    del wls
     out = {}
     stream = run.stream
     for label, reroute in (("sere", True), ("no_reroute", False)):
-        def one_pass(with_outputs):
-            for layer in layers:
-                if reroute:
-                    layer.run_decode(stream, with_outputs)
-                else:
-                    layer.run_baseline(stream, with_outputs)
         with torch.cuda.stream(stream):
-            one_pass(True)
+            stk.run(stream, reroute, True)
             stream.synchronize()
-            counts = [layer.route.num_active.cpu().tolist() for layer in layers]
+            counts = stk.active_counts()
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
-                one_pass(False)
+                stk.run(stream, reroute, False)
             for _ in range(3):
                 graph.replay()
-            reps = max(1, args.steps // args.layers)
+            reps = max(4, args.steps // args.layers)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             e0.record(stream)
@@ -509,6 +501,7 @@ def stack(args, run, S, rho):
         out[label] = {"us_per_pass": round(us, 2), "us_per_layer": round(us / args.layers, 2),
                       "active_before": [c[0] for c in counts], "active_after": [c[1] for c in counts]}
     out["layers"] = args.layers
+    out["weights"] = "independent per layer; one similarity matrix per layer (sere_similarity on that layer's weights)"
     out["speedup_vs_no_reroute"] = round(out["no_reroute"]["us_per_pass"] / out["sere"]["us_per_pass"], 3)
     return out
 
@@ -528,6 +521,21 @@ def sweep(args, batches=None):
             nb, na = run.active(mode)
             us, _, _, _ = run.time(mode, 200 if T <= 256 else 40, 20 if T <= 256 else 4)
             row[label] = {"us_per_step": round(us, 2), "active": nb if mode == "baseline" else na}
+            if T >= 512 and label == "S=2":
+                # prefill-sized: the expert FFN against both of its bounds, the matrix cores
+                # (6 d_h d_m flop per slot) and the weight stream (every active expert once)
+                sp = wl.spec
+                st = run.stage_times(mode, 20)
+                ffn_us = st["gate_up"] + st["down"]
+                flop = 6.0 * sp.hidden * sp.inter * T * sp.top_k
+                wbytes = na * sp.expert_bytes
+                row["ffn_roofline"] = {
+                    "stage_us": {k: round(v, 2) for k, v in st.items() if v},
+                    "mfma": {"bound": "mfma", "achieved": round(flop / ffn_us * 1e-6, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                             "frac": round(flop / ffn_us * 1e-6 / 2500.0, 4)},
+                    "hbm": {"bound": "hbm", "achieved": round(wbytes / ffn_us * 1e-3, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": round(wbytes / ffn_us * 1e-3 / HBM_PEAK_GBS, 4)},
+                    "binding": "hbm" if wbytes / HBM_PEAK_GBS * 1e-3 > flop / 2500.0 * 1e-6 else "mfma"}
         out[str(T)] = row
         del run
     return out

@@ -468,7 +468,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
 
 // ------------------------------------------------------------- similarity ---
 struct SimLayout {
-  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, gram, rowsum, diag, gram_part, twins,
+  size_t sorted_token, work_expert, work_off, work_cnt, n_work, h, y, dist, acc, gram, rowsum, diag, gram_part, max_bits,
       total;
   int rows, ksplit;
   int gram_splits;      // Frobenius metric: slices of the flattened outputs in the Gram kernel
@@ -495,6 +495,7 @@ static SimLayout make_sim_layout(const sere_config& c, int n) {
   l.y = take(static_cast<size_t>(l.ksplit) * R * c.hidden * sizeof(float));
   l.dist = take(M * M * sizeof(double));
   l.acc = take(M * M * sizeof(double));
+  l.max_bits = take(8);
   if (c.flags & SERE_FLAG_SIM_CKA_LINEAR) {  // Gram matrix and its row sums per expert
     l.gram = take(R * n * sizeof(double));
     l.rowsum = take(R * sizeof(double));
@@ -502,12 +503,16 @@ static SimLayout make_sim_layout(const sere_config& c, int n) {
   }
   if ((c.flags & (SERE_FLAG_SIM_CKA_LINEAR | SERE_FLAG_SIM_COSINE)) == 0) {  // Frobenius: partial Gram matrices of the experts
     const long long L = static_cast<long long>(n) * c.hidden;
-    long long chunk = (L + kGramMaxSplits - 1) / kGramMaxSplits;
-    chunk = std::max<long long>(256, (chunk + 15) / 16 * 16);
+    // enough splits that blocks x splits fill the chip (about 512 workgroups), 16 .. 128 of them,
+    // each a multiple of the Gram kernel's 64-wide load group
+    const int nb = static_cast<int>((M + kGramBlock - 1) / kGramBlock);
+    const int want = std::min(128, std::max(16, 512 / (nb * (nb + 1) / 2)));
+    long long chunk = (L + want - 1) / want;
+    chunk = std::max<long long>(256, (chunk + 63) / 64 * 64);
     l.gram_chunk = chunk;
     l.gram_splits = static_cast<int>((L + chunk - 1) / chunk);
-    l.gram_part = take(static_cast<size_t>(l.gram_splits) * M * M * sizeof(double));
-    l.twins = take((1 + 2 * M * M) * sizeof(int32_t));
+    l.gram_part = take(static_cast<size_t>(l.gram_splits) * gram_part_stride(static_cast<int>(M)) * sizeof(double));
+    l.gram = take(kGramGroups * M * M * sizeof(double));
   }
   l.total = o;
   return l;
@@ -570,6 +575,7 @@ static int similarity(const sere_config* cfg, const void* calib, int32_t num_bat
                          ? kMetricCosine
                          : ((cfg->flags & SERE_FLAG_SIM_CKA_LINEAR) ? kMetricCkaLinear : kMetricFrobenius);
   double* dist = reinterpret_cast<double*>(ws + l.dist);
+  unsigned long long* max_bits = reinterpret_cast<unsigned long long*>(ws + l.max_bits);
   for (int b = 0; b < num_batches; ++b) {
     f.hidden = static_cast<const char*>(calib) + static_cast<size_t>(b) * n * cfg->hidden * eb;
     launch_gateup_down(cfg->dtype, cfg->inter, cfg->hidden, M, l.ksplit, f, s);
@@ -592,19 +598,20 @@ static int similarity(const sere_config* cfg, const void* calib, int32_t num_bat
       hipLaunchKernelGGL(pair_hsic_kernel, dim3(M, M), dim3(256), 0, s, gram, rowsum, n, M, dist);
     } else {
       double* part = reinterpret_cast<double*>(ws + l.gram_part);
-      int32_t* twins = reinterpret_cast<int32_t*>(ws + l.twins);
+      double* gram = reinterpret_cast<double*>(ws + l.gram);
       const int nb = (M + kGramBlock - 1) / kGramBlock;
-      launch_stage(SERE_STAGE_SIM_PAIRS, s, clear_word_kernel, dim3(1), dim3(64), twins);
+      const dim3 per_pair((M * M + 255) / 256);
       launch_stage(SERE_STAGE_SIM_PAIRS, s, frobenius_gram_kernel, dim3(nb * (nb + 1) / 2, l.gram_splits), dim3(256), f.y,
-                   l.ksplit, l.rows, n, cfg->hidden, M, l.gram_chunk, part);
-      launch_stage(SERE_STAGE_SIM_PAIRS, s, frobenius_from_gram_kernel, dim3((M * M + 255) / 256), dim3(256), part,
-                   l.gram_splits, M, dist, twins);
-      launch_stage(SERE_STAGE_SIM_PAIRS, s, pair_distance_kernel, dim3(256), dim3(256), f.y, l.ksplit, l.rows, n,
-                   cfg->hidden, M, static_cast<const int32_t*>(twins), dist);
+                   l.ksplit, l.rows, n, cfg->hidden, M, l.gram_chunk, part, max_bits);
+      launch_stage(SERE_STAGE_SIM_PAIRS, s, gram_reduce_kernel, dim3(per_pair.x, kGramGroups), dim3(256),
+                   static_cast<const double*>(part), l.gram_splits, M, gram);
+      launch_stage(SERE_STAGE_SIM_PAIRS, s, frobenius_distance_kernel, per_pair, dim3(256),
+                   static_cast<const double*>(gram), static_cast<const float*>(f.y), l.ksplit, l.rows, n, cfg->hidden,
+                   M, dist, max_bits);
     }
-    launch_stage(SERE_STAGE_SIM_PAIRS, s, similarity_accumulate_kernel, dim3(1), dim3(1024),
+    launch_stage(SERE_STAGE_SIM_PAIRS, s, similarity_accumulate_kernel, dim3((M * M + 255) / 256), dim3(256),
                  static_cast<const double*>(dist), M, b, static_cast<int>(num_batches), metric,
-                 reinterpret_cast<double*>(ws + l.acc), sim);
+                 static_cast<const unsigned long long*>(max_bits), reinterpret_cast<double*>(ws + l.acc), sim);
   }
   return hip_status();
 }

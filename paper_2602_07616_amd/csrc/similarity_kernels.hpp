@@ -30,11 +30,6 @@ __global__ __launch_bounds__(256) void similarity_worklist_kernel(int M, int n, 
   }
 }
 
-// a fill kernel for one counter word (usable under graph capture, where a memset node is not)
-__global__ void clear_word_kernel(int32_t* word) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *word = 0;
-}
-
 // Frobenius distances of all pairs (appendix "Frobenius Similarity"), x_pq = ||A_p - A_q||_F, from
 // the Gram matrix of the experts' outputs: with V_e the output of expert e on the batch, flattened
 // to one vector of L = n * d_h numbers (A_e = sum over slices of y[slice][e*n .. e*n+n) rows),
@@ -43,10 +38,14 @@ __global__ void clear_word_kernel(int32_t* word) {
 // (v_mfma_f64_16x16x4: products of fp32 numbers are exact in fp64, sums carry ~1e-16 relative
 // rounding each), so the cancellation in the formula above costs at most ~1e-15 of an output's
 // squared norm: harmless for every pair but near-identical twins, which are recomputed as a
-// direct difference (pair_distance_kernel on a list of flagged pairs).
+// direct difference by the wavefront that finds them.
 typedef double f64x4 __attribute__((ext_vector_type(4)));
-constexpr int kGramBlock = 32;     // experts per side of a workgroup's block (2 x 2 tiles of 16 x 16, one per wavefront)
-constexpr int kGramMaxSplits = 64; // slices of L, so that M = 128 gives 10 x 64 workgroups
+constexpr int kGramBlock = 64;     // experts per side of a workgroup's block: 2 x 2 wavefronts, each 2 x 2 tiles of 16 x 16
+constexpr int kGramSteps = 2;      // 16-wide k steps per load group (two groups are in flight)
+// partial Gram matrices lie M * M + kGramPad doubles apart: a power-of-two distance would put the
+// same entry of every split on the same memory channel
+constexpr int kGramPad = 96;
+__host__ __device__ inline size_t gram_part_stride(int M) { return static_cast<size_t>(M) * M + kGramPad; }
 constexpr double kGramTwinThreshold = 1e-9;  // x_pq^2 below this fraction of <V_p,V_p> + <V_q,V_q>: recompute directly
 
 // upper-triangular blocks (bp <= bq) numbered row by row
@@ -60,97 +59,152 @@ __device__ __forceinline__ void gram_block_of(int index, int nb, int& bp, int& b
 }
 
 // part[split][p][q] = sum over the split's range of L of V_p[k] * V_q[k], for every (p, q) of the
-// upper-triangular 32 x 32 blocks.  grid (nb (nb + 1) / 2, nsplit), 256 threads; lane l of a
-// wavefront holds row l % 16 of its tile, and of every 16 consecutive k the four l / 16 ... (the
-// order of k inside the sum is free as long as both operands agree).
+// upper-triangular 64 x 64 blocks.  grid (nb (nb + 1) / 2, nsplit), 256 threads; lane l of a
+// wavefront holds row l % 16 of each of its tiles, and of every 16 consecutive k the four
+// 4 (l / 16) ... + 3 (the order of k inside the sum is free as long as both operands agree).
+// `chunk` (the split's length) is a multiple of 2 * 16 * kGramSteps (= 64, as L is).
 __global__ __launch_bounds__(256) void frobenius_gram_kernel(const float* __restrict__ y, int ksplit, int rows, int n,
                                                              int dh, int M, long long chunk,
-                                                             double* __restrict__ part) {
+                                                             double* __restrict__ part,
+                                                             unsigned long long* __restrict__ max_bits) {
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *max_bits = 0ull;   // for frobenius_distance_kernel
   const int nb = (M + kGramBlock - 1) / kGramBlock;
   int bp, bq;
   gram_block_of(blockIdx.x, nb, bp, bq);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r16 = lane & 15, kq = lane >> 4;
-  const int p0 = bp * kGramBlock + (wave >> 1) * 16, q0 = bq * kGramBlock + (wave & 1) * 16;
+  const int p0 = bp * kGramBlock + (wave >> 1) * 32, q0 = bq * kGramBlock + (wave & 1) * 32;
   const long long L = static_cast<long long>(n) * dh;             // multiple of 64
   const size_t slice = static_cast<size_t>(rows) * dh;
-  const float* ap = y + static_cast<size_t>(min(p0 + r16, M - 1)) * L + 4 * kq;   // rows beyond M repeat the last one (unused)
-  const float* aq = y + static_cast<size_t>(min(q0 + r16, M - 1)) * L + 4 * kq;
-  const long long kbeg = blockIdx.y * chunk, kend = min(kbeg + chunk, L);       // chunk: multiple of 16
-  f64x4 acc = {0.0, 0.0, 0.0, 0.0};
-  for (long long k = kbeg; k < kend; k += 16) {
-    float4 a = *reinterpret_cast<const float4*>(ap + k), b = *reinterpret_cast<const float4*>(aq + k);
+  const float* ap[2];
+  const float* aq[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {   // rows beyond M repeat the last one (their results are not stored)
+    ap[t] = y + static_cast<size_t>(min(p0 + 16 * t + r16, M - 1)) * L + 4 * kq;
+    aq[t] = y + static_cast<size_t>(min(q0 + 16 * t + r16, M - 1)) * L + 4 * kq;
+  }
+  const long long kbeg = blockIdx.y * chunk, kend = min(kbeg + chunk, L);
+  auto fetch = [&](const float* row, long long k) {
+    float4 v = *reinterpret_cast<const float4*>(row + k);
     for (int s = 1; s < ksplit; ++s) {
-      const float4 a2 = *reinterpret_cast<const float4*>(ap + s * slice + k);
-      const float4 b2 = *reinterpret_cast<const float4*>(aq + s * slice + k);
-      a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
-      b.x += b2.x; b.y += b2.y; b.z += b2.z; b.w += b2.w;
+      const float4 v2 = *reinterpret_cast<const float4*>(row + s * slice + k);
+      v.x += v2.x; v.y += v2.y; v.z += v2.z; v.w += v2.w;
     }
-    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(a.x), static_cast<double>(b.x), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(a.y), static_cast<double>(b.y), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(a.z), static_cast<double>(b.z), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(a.w), static_cast<double>(b.w), acc, 0, 0, 0);
+    return v;
+  };
+  f64x4 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) acc[a][b] = f64x4{0.0, 0.0, 0.0, 0.0};
+  // groups of kGramSteps steps, double buffered: the loads of the next group are in flight while
+  // the current one is multiplied (the split's length is a multiple of 2 * 16 * kGramSteps)
+  float4 va[2][kGramSteps][2], vb[2][kGramSteps][2];
+  auto fetch_group = [&](int buf, long long k) {
+#pragma unroll
+    for (int st = 0; st < kGramSteps; ++st)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        va[buf][st][t] = fetch(ap[t], k + 16 * st);
+        vb[buf][st][t] = fetch(aq[t], k + 16 * st);
+      }
+  };
+  auto multiply_group = [&](int buf) {
+#pragma unroll
+    for (int st = 0; st < kGramSteps; ++st)
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const float4 x = va[buf][st][a], w = vb[buf][st][b];
+          acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(x.x), static_cast<double>(w.x), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(x.y), static_cast<double>(w.y), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(x.z), static_cast<double>(w.z), acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(x.w), static_cast<double>(w.w), acc[a][b], 0, 0, 0);
+        }
+  };
+  constexpr int kGroup = 16 * kGramSteps;
+  fetch_group(0, kbeg);
+  for (long long k = kbeg; k < kend; k += 2 * kGroup) {
+    fetch_group(1, k + kGroup);                               // in range: the split holds whole pairs of groups
+    multiply_group(0);
+    fetch_group(0, k + 2 * kGroup < kend ? k + 2 * kGroup : kbeg);   // after the last pair: a harmless re-read
+    multiply_group(1);
   }
   // lane l holds D[l / 16 + 4 r][l % 16], r = 0..3 (the fp64 tile interleaves its row blocks)
-  double* out = part + static_cast<size_t>(blockIdx.y) * M * M;
+  double* out = part + static_cast<size_t>(blockIdx.y) * gram_part_stride(M);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int pp = p0 + kq + 4 * r, qq = q0 + r16;
-    if (pp < M && qq < M) out[static_cast<size_t>(pp) * M + qq] = acc[r];
-  }
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int pp = p0 + 16 * a + kq + 4 * r, qq = q0 + 16 * b + r16;
+        if (pp < M && qq < M) out[static_cast<size_t>(pp) * M + qq] = acc[a][b][r];
+      }
 }
 
-// dist[p][q] = sqrt(G_pp + G_qq - 2 G_pq) with G = the sum of the partial Gram matrices in fixed
-// order (entries below the block diagonal are read from their mirror image).  A pair whose squared
-// distance is below kGramTwinThreshold of G_pp + G_qq (near-identical outputs: the subtraction has
-// cancelled most digits) is put on the `twins` list instead: twins[0] = count, then (p, q) pairs;
-// its dist entry is filled by pair_distance_kernel.  *twins must be 0 at launch.
-// grid ceil(M * M / 256), 256 threads.
-__global__ __launch_bounds__(256) void frobenius_from_gram_kernel(const double* __restrict__ part, int nsplit, int M,
-                                                                  double* __restrict__ dist, int32_t* twins) {
+// The partial Gram matrices are added in two fixed-order levels: group r of kGramGroups takes the
+// splits r, r + kGramGroups, ... (this kernel; entries below the block diagonal are read from
+// their mirror image), and the distance kernel adds the kGramGroups group sums.
+// grid (ceil(M * M / 256), kGramGroups), 256 threads.
+constexpr int kGramGroups = 8;
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const double* __restrict__ part, int nsplit, int M,
+                                                          double* __restrict__ gram) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= M * M) return;
-  const int p = idx / M, q = idx % M;
-  auto gram = [&](int a, int b) {
-    if (a / kGramBlock > b / kGramBlock) {
-      const int t = a;
-      a = b;
-      b = t;
-    }
-    double g = 0.0;
-    for (int s = 0; s < nsplit; ++s) g += part[(static_cast<size_t>(s) * M + a) * M + b];
-    return g;
-  };
-  double d = 0.0;
-  if (p != q) {
-    const double gpp = gram(p, p), gqq = gram(q, q), gpq = gram(p, q);
-    const double d2 = (gpp + gqq) - 2.0 * gpq;
-    if (d2 < kGramTwinThreshold * (gpp + gqq)) {
-      const int at = atomicAdd(twins, 1);
-      twins[1 + 2 * at] = p;
-      twins[2 + 2 * at] = q;
-    } else {
-      d = sqrt(d2);
-    }
+  int a = idx / M, b = idx % M;
+  if (a / kGramBlock > b / kGramBlock) {
+    const int t = a;
+    a = b;
+    b = t;
   }
-  dist[idx] = d;
+  const size_t mm = gram_part_stride(M);
+  const double* src = part + static_cast<size_t>(a) * M + b;
+  double g = 0.0;
+  for (int s = blockIdx.y; s < nsplit; s += kGramGroups) g += src[s * mm];
+  gram[static_cast<size_t>(blockIdx.y) * M * M + idx] = g;
 }
 
-// dist[p][q] = sqrt(sum_i (A_p[i] - A_q[i])^2) as a direct difference, for the pairs on the twins
-// list.  grid: any number of workgroups (they stride over the list), 256 threads; fp64 accumulation.
-__global__ __launch_bounds__(256) void pair_distance_kernel(const float* __restrict__ y, int ksplit, int rows,
-                                                            int n, int dh, int M, const int32_t* __restrict__ twins,
-                                                            double* __restrict__ dist) {
-  __shared__ double part[4];
-  const int count = twins[0];
+// dist[p][q] = sqrt(G_pp + G_qq - 2 G_pq), G = the sum of the group sums `gram`.  A pair whose squared distance is below
+// kGramTwinThreshold of G_pp + G_qq (near-identical outputs: the subtraction has cancelled most
+// digits) is recomputed as a direct difference sqrt(sum_i (A_p[i] - A_q[i])^2) by the whole
+// wavefront, one such pair after the other.  The largest distance of the batch is gathered in
+// *max_bits (the bits of a non-negative double order like the number; cleared by the Gram kernel).
+// grid ceil(M * M / 256), 256 threads.
+__global__ __launch_bounds__(256) void frobenius_distance_kernel(const double* __restrict__ gram,
+                                                                 const float* __restrict__ y, int ksplit, int rows,
+                                                                 int n, int dh, int M, double* __restrict__ dist,
+                                                                 unsigned long long* __restrict__ max_bits) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const bool valid = idx < M * M;
+  const int p = valid ? idx / M : 0, q = valid ? idx % M : 0;
+  double d = 0.0;
+  bool twin = false;
+  auto entry = [&](int at) {   // the group sums of one entry, in fixed order
+    double g = 0.0;
+#pragma unroll
+    for (int r = 0; r < kGramGroups; ++r) g += gram[static_cast<size_t>(r) * M * M + at];
+    return g;
+  };
+  if (valid && p != q) {
+    const double gpp = entry(p * M + p), gqq = entry(q * M + q);
+    const double d2 = (gpp + gqq) - 2.0 * entry(idx);
+    twin = d2 < kGramTwinThreshold * (gpp + gqq);
+    if (!twin) d = sqrt(d2);
+  }
+  unsigned long long todo = __ballot(twin);
   const size_t len = static_cast<size_t>(n) * dh;          // multiple of 64
   const size_t slice = static_cast<size_t>(rows) * dh;
-  for (int t = blockIdx.x; t < count; t += gridDim.x) {
-    const int p = twins[1 + 2 * t], q = twins[2 + 2 * t];
-    const float* ap = y + static_cast<size_t>(p) * len;
-    const float* aq = y + static_cast<size_t>(q) * len;
+  while (todo != 0ull) {                                   // wave-uniform
+    const int src = __ffsll(static_cast<long long>(todo)) - 1;
+    todo &= todo - 1ull;
+    const int tp = __shfl(p, src, kWave), tq = __shfl(q, src, kWave);
+    const float* ap = y + static_cast<size_t>(tp) * len;
+    const float* aq = y + static_cast<size_t>(tq) * len;
     double acc = 0.0;
-    for (size_t i = static_cast<size_t>(threadIdx.x) * 4; i < len; i += 1024) {
+    for (size_t i = static_cast<size_t>(lane) * 4; i < len; i += 256) {
       float4 a = *reinterpret_cast<const float4*>(ap + i), b = *reinterpret_cast<const float4*>(aq + i);
       for (int s = 1; s < ksplit; ++s) {
         const float4 a2 = *reinterpret_cast<const float4*>(ap + s * slice + i);
@@ -163,11 +217,13 @@ __global__ __launch_bounds__(256) void pair_distance_kernel(const float* __restr
       acc += dx * dx + dy * dy + dz * dz + dw * dw;
     }
     acc = wave_sum(acc);
-    __syncthreads();   // part[] of the previous pair has been read
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) dist[static_cast<size_t>(p) * M + q] = sqrt((part[0] + part[1]) + (part[2] + part[3]));
+    if (lane == src) d = sqrt(acc);
   }
+  if (valid) dist[idx] = d;
+  double m = d;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = fmax(m, __shfl_xor(m, off, kWave));
+  if (lane == 0 && m > 0.0) atomicMax(max_bits, static_cast<unsigned long long>(__double_as_longlong(m)));
 }
 
 // Cosine metric (appendix "Cosine Similarity"): out[p][q] = (1/n) sum over tokens i of
@@ -335,38 +391,31 @@ __global__ __launch_bounds__(256) void pair_hsic_kernel(const double* __restrict
 
 constexpr int kMetricFrobenius = 0, kMetricCosine = 1, kMetricCkaLinear = 2;
 
-// Frobenius: acc[p][q] (+)= 1 - dist/max(dist); cosine: acc[p][q] (+)= dist[p][q] (the pair
-// kernel's value as it is); linear CKA: acc[p][q] (+)= dist[p][q] / sqrt(dist[p][p] dist[q][q]),
-// dist holding the HSIC estimates (0 where a self-term is not positive: the quotient is undefined
-// there).  On the last batch sim = acc / N.  One block of 1024 threads.
-__global__ __launch_bounds__(1024) void similarity_accumulate_kernel(const double* __restrict__ dist, int M,
-                                                                     int batch, int num_batches, int metric,
-                                                                     double* __restrict__ acc,
-                                                                     float* __restrict__ sim) {
-  __shared__ double smax[16];
-  const int total = M * M;
-  double m = 0.0;
-  for (int i = threadIdx.x; i < total; i += 1024) m = fmax(m, dist[i]);
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) m = fmax(m, __shfl_xor(m, off, kWave));
-  if ((threadIdx.x & 63) == 0) smax[threadIdx.x >> 6] = m;
-  __syncthreads();
-  double mx = 0.0;
-  for (int w = 0; w < 16; ++w) mx = fmax(mx, smax[w]);
-  for (int i = threadIdx.x; i < total; i += 1024) {
-    double sv;
-    if (metric == kMetricCosine) {
-      sv = dist[i];
-    } else if (metric == kMetricCkaLinear) {
-      const double hp = dist[static_cast<size_t>(i / M) * M + i / M], hq = dist[static_cast<size_t>(i % M) * M + i % M];
-      sv = (hp > 0.0 && hq > 0.0) ? dist[i] / sqrt(hp * hq) : 0.0;
-    } else {
-      sv = mx > 0.0 ? 1.0 - dist[i] / mx : 1.0;  // all pairs identical: Sim = 1
-    }
-    const double a = (batch == 0 ? 0.0 : acc[i]) + sv;
-    acc[i] = a;
-    if (batch == num_batches - 1) sim[i] = static_cast<float>(a / num_batches);
+// Frobenius: acc[p][q] (+)= 1 - dist/max(dist), the maximum of the batch given as the bits of a
+// double in *max_bits; cosine: acc[p][q] (+)= dist[p][q] (the pair kernel's value as it is); linear
+// CKA: acc[p][q] (+)= dist[p][q] / sqrt(dist[p][p] dist[q][q]), dist holding the HSIC estimates (0
+// where a self-term is not positive: the quotient is undefined there).  On the last batch
+// sim = acc / N.  grid ceil(M * M / 256), 256 threads.
+__global__ __launch_bounds__(256) void similarity_accumulate_kernel(const double* __restrict__ dist, int M,
+                                                                    int batch, int num_batches, int metric,
+                                                                    const unsigned long long* __restrict__ max_bits,
+                                                                    double* __restrict__ acc,
+                                                                    float* __restrict__ sim) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * M) return;
+  double sv;
+  if (metric == kMetricCosine) {
+    sv = dist[i];
+  } else if (metric == kMetricCkaLinear) {
+    const double hp = dist[static_cast<size_t>(i / M) * M + i / M], hq = dist[static_cast<size_t>(i % M) * M + i % M];
+    sv = (hp > 0.0 && hq > 0.0) ? dist[i] / sqrt(hp * hq) : 0.0;
+  } else {
+    const double mx = __longlong_as_double(static_cast<long long>(*max_bits));
+    sv = mx > 0.0 ? 1.0 - dist[i] / mx : 1.0;  // all pairs identical: Sim = 1
   }
+  const double a = (batch == 0 ? 0.0 : acc[i]) + sv;
+  acc[i] = a;
+  if (batch == num_batches - 1) sim[i] = static_cast<float>(a / num_batches);
 }
 
 }  // namespace sere

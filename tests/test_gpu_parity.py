@@ -667,7 +667,7 @@ def test_stage_timing_reports_every_stage(dev):
     ms, n = B.sere_stage_timing_read()
     B.sere_stage_timing(False)
     batches = wl.calib.shape[0]
-    assert n["gate_up"] == batches and n["down"] == batches and n["sim_pairs"] == 5 * batches, n
+    assert n["gate_up"] == batches and n["down"] == batches and n["sim_pairs"] == 4 * batches, n
     assert ms["sim_pairs"] > 0
 
 
