@@ -162,40 +162,53 @@ void oracle_primary_mask(const int32_t *ids, int T, int K, int S, int M, int32_t
 }
 
 /*
- * Re-routing, one (token, secondary slot) at a time, as the appendix
- * algorithm states it: retained experts stay; otherwise scan the retained
- * experts in ascending index, keep the strictly largest similarity (start:
- * -inf, expert 0), and keep the original expert only if rho > 0 and the best
- * similarity is below rho.
+ * Row `row` = similarities of one expert to all M experts.  Visits the experts
+ * marked in `primary` in ascending index; a later one displaces the current
+ * choice only when it is strictly more similar (so equal similarities go to
+ * the lower index).  With no marked expert, or none whose similarity exceeds
+ * the value passed in, *choice and *value stay as the caller set them.
+ */
+static void most_similar_primary(const float *row, const int32_t *primary, int M,
+                                 int *choice, float *value)
+{
+    for (int v = 0; v < M; ++v) {
+        if (!primary[v])
+            continue;
+        if (row[v] > *value) {
+            *value = row[v];
+            *choice = v;
+        }
+    }
+}
+
+/*
+ * Re-routing seen from the slots (Sec. 3.2.2 Steps 1-2 and the appendix
+ * algorithm's contract: top-K indices in, indices out).  Every slot of rank
+ * >= S whose expert is in nobody's top-S gets the most similar primary in its
+ * place, unless the threshold test is on (rho > 0) and that similarity is
+ * below rho.  The search starts from (-inf, expert 0), which is also its
+ * result when no similarity is above -inf.
  */
 void oracle_reroute_per_slot(const int32_t *ids, const float *sim, int T, int K,
                              int M, int S, float rho, int32_t *ids_out)
 {
-    int32_t *H = (int32_t *)malloc(sizeof(int32_t) * (size_t)M);
-    oracle_primary_mask(ids, T, K, S, M, H);
-    for (size_t a = 0; a < (size_t)T * K; ++a)
-        ids_out[a] = ids[a];
-    for (int t = 0; t < T; ++t)
-        for (int k = S; k < K; ++k) {
-            int e_orig = ids[(size_t)t * K + k];
-            if (H[e_orig])
-                continue;
-            float s_best = -INFINITY;
-            int e_best = 0;
-            for (int e = 0; e < M; ++e)
-                if (H[e]) {
-                    float s = sim[(size_t)e_orig * M + e];
-                    if (s > s_best) {
-                        s_best = s;
-                        e_best = e;
-                    }
-                }
-            if (rho > 0.0f && s_best < rho)
-                ids_out[(size_t)t * K + k] = e_orig;
-            else
-                ids_out[(size_t)t * K + k] = e_best;
-        }
-    free(H);
+    int32_t *primary = (int32_t *)malloc(sizeof(int32_t) * (size_t)M);
+    oracle_primary_mask(ids, T, K, S, M, primary);
+    const int threshold_on = rho > 0.0f;
+    for (size_t slot = 0; slot < (size_t)T * K; ++slot) {
+        const int rank = (int)(slot % (size_t)K);
+        const int u = ids[slot];
+        ids_out[slot] = u;
+        if (rank < S || primary[u])
+            continue;                    /* top-S slot, or retained by some token */
+        int v = 0;
+        float closeness = -INFINITY;
+        most_similar_primary(sim + (size_t)u * M, primary, M, &v, &closeness);
+        const int critical = threshold_on && closeness < rho;
+        if (!critical)
+            ids_out[slot] = v;
+    }
+    free(primary);
 }
 
 /*

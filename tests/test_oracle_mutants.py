@@ -19,12 +19,14 @@ MUTANTS = [
     ("gate_not_normalised", "- top) / denom;", "- top);", [pins.pin_topk_order_and_gate]),
     ("primary_only_top1", "for (int s = 0; s < S; ++s)", "for (int s = 0; s < 1; ++s)",
      [pins.pin_reroute_against_brute]),
-    ("slot_sim_transposed", "sim[(size_t)e_orig * M + e]", "sim[(size_t)e * M + e_orig]",
+    ("slot_sim_transposed", "most_similar_primary(sim + (size_t)u * M, primary, M, &v, &closeness);",
+     "{ float col[256]; for (int c = 0; c < M; ++c) col[c] = sim[(size_t)c * M + u];\n"
+     "          most_similar_primary(col, primary, M, &v, &closeness); }",
      [pins.pin_reroute_hand_cases]),
-    ("slot_tie_high_index", "if (s > s_best)", "if (s >= s_best)", [pins.pin_reroute_hand_cases]),
-    ("slot_threshold_inclusive", "rho > 0.0f && s_best < rho", "rho > 0.0f && s_best <= rho",
+    ("slot_tie_high_index", "if (row[v] > *value) {", "if (row[v] >= *value) {", [pins.pin_reroute_hand_cases]),
+    ("slot_threshold_inclusive", "threshold_on && closeness < rho;", "threshold_on && closeness <= rho;",
      [pins.pin_reroute_hand_cases]),
-    ("slot_rho0_not_disabled", "if (rho > 0.0f && s_best < rho)", "if (s_best <= rho)",
+    ("slot_rho0_not_disabled", "const int critical = threshold_on && closeness < rho;", "const int critical = closeness <= rho;",
      [pins.pin_reroute_against_brute]),
     ("sets_sim_transposed", "sim[(size_t)u * M + v] > sim[(size_t)u * M + v_star]",
      "sim[(size_t)v * M + u] > sim[(size_t)v_star * M + u]", [pins.pin_reroute_hand_cases]),
@@ -32,7 +34,7 @@ MUTANTS = [
      [pins.pin_reroute_hand_cases]),
     ("sets_critical_not_preserved", "final_set[u] = 1;           /* critical expert: preserved */",
      "final_set[u] = 0;", [pins.pin_fig2_behaviour]),
-    ("slot_retained_rerouted", "if (H[e_orig])\n                continue;", "",
+    ("slot_retained_rerouted", "if (rank < S || primary[u])", "if (rank < S)",
      [pins.pin_reroute_hand_cases]),
     ("compact_slot_major", "for (int t = 0; t < T; ++t)\n            for (int k = 0; k < K; ++k)\n                if (ids[(size_t)t * K + k] == e) {",
      "for (int k = 0; k < K; ++k)\n            for (int t = 0; t < T; ++t)\n                if (ids[(size_t)t * K + k] == e) {",
