@@ -17,6 +17,7 @@ Qwen1.5-MoE-shaped one) with its (S, rho) grid from the paper's main tables.
 from __future__ import annotations
 
 import argparse
+from dataclasses import replace
 import json
 import os
 import statistics
@@ -63,6 +64,8 @@ def parse():
                     help=f"headline workload (default {HEADLINE}); naming one implies --only-headline")
     ap.add_argument("--only-headline", action="store_true",
                     help="skip the other layer shapes of the \"configs\" object")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="with --workload: batch size T in place of the workload's own (same layer, same seeds)")
     ap.add_argument("--S", type=int, default=0, help="select_top_k of the headline SERE step (0: the workload's first grid setting)")
     ap.add_argument("--rho", type=float, default=0.0, help="threshold of the headline SERE step")
     ap.add_argument("--copies", type=int, default=0, help="weight copies to rotate over (0: auto)")
@@ -70,6 +73,8 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep")
     ap.add_argument("--prefill", action="store_true",
                     help="also time prefill-sized batches (512, 1024, 2048 tokens) of the Qwen3-shaped layer")
+    ap.add_argument("--batches", default="",
+                    help="with --prefill: comma-separated batch sizes in place of 512,1024,2048")
     ap.add_argument("--rho-sweep", action="store_true",
                     help="also time thresholds 0.0 .. 1.0 at select_top_k = 1 (active experts and us)")
     ap.add_argument("--layers", type=int, default=0,
@@ -281,7 +286,7 @@ def cpu_baseline(wl, sim, S, rho, budget_s):
         step()
         times.append(time.perf_counter() - t0)
     return {"value": round(min(times) * 1e6, 1), "unit": "us/step", "cores": threads, "kind": "oracle",
-            "sample": f"{len(times)} full SERE steps (S={S}, rho={rho}) of {sp.name} on all host threads, best of",
+            "sample": f"{len(times)} full SERE steps (S={S}, rho={rho}) of {sp.name} on all host threads; value = fastest step, mean_us = their mean",
             "mean_us": round(statistics.mean(times) * 1e6, 1)}
 
 
@@ -292,6 +297,8 @@ def measure_config(args, name, S, rho, steps, warmup, headline):
     import numpy as np
     from paper_2602_07616_amd import workloads as wk
     spec = wk.SPECS[name]
+    if headline and args.tokens > 0 and args.workload:
+        spec = replace(spec, name=f"{spec.name}@T{args.tokens}", tokens=args.tokens)
     wl = wk.make_workload(spec)
     eb = spec.elem_bytes
     expert_bytes = spec.expert_bytes
@@ -459,7 +466,8 @@ def main():
     if args.sweep:
         result["sweep"] = sweep(args)
     if args.prefill:
-        result["prefill_sized"] = sweep(args, (512, 1024, 2048))
+        batches = tuple(int(b) for b in args.batches.split(",")) if args.batches else (512, 1024, 2048)
+        result["prefill_sized"] = sweep(args, batches)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, sim_host, S, rho, args.cpu_seconds)
     print(json.dumps(result))

@@ -115,6 +115,8 @@ struct Stage {
 };
 // the largest configuration (eight token tiles, 64-wide chunks), two buffers
 constexpr int kStageLdsBytes = 2 * Stage<8, 64>::kBufBytes;
+// the kernels for prefill-sized batches stage 128-wide chunks of up to eight token tiles
+constexpr int kWideLdsBytes = 2 * Stage<8, 128>::kBufBytes;
 static_assert(Stage<8, 64>::kBufBytes >= Stage<4, 128>::kBufBytes && Stage<8, 64>::kBufBytes >= Stage<2, 256>::kBufBytes,
               "LDS budget");
 
@@ -143,7 +145,7 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
   using St = Stage<NT, KC>;
   constexpr int KB = KC / 64;          // 64-wide k blocks per chunk
   constexpr int NP = LO ? 2 : 1;
-  static_assert(NP * 2 * St::kBufBytes <= kStageLdsBytes, "LDS budget");
+  static_assert(NP * 2 * St::kBufBytes <= kWideLdsBytes, "LDS budget");
   const int tid = threadIdx.x, lane = tid & 63;
   const int i = lane & 15, g = lane >> 4;
   const int len = kend - kbeg;
@@ -264,10 +266,11 @@ __device__ __forceinline__ BlockMap map_block(bool fine, int coarse_parts) {
 }
 
 // first chunk of a workgroup: spread over the row
-__device__ __forceinline__ int start_rotation(int len, int chunk) {
+// seed < 0: the workgroup's linear id
+__device__ __forceinline__ int start_rotation(int len, int chunk, int seed = -1) {
   const int n = (len + chunk - 1) / chunk;
   if (n <= 1) return 0;
-  const unsigned id = blockIdx.y * gridDim.x + blockIdx.x;
+  const unsigned id = seed < 0 ? blockIdx.y * gridDim.x + blockIdx.x : static_cast<unsigned>(seed);
   return static_cast<int>((id * 5u) % static_cast<unsigned>(n));
 }
 
@@ -281,7 +284,7 @@ __device__ __forceinline__ int start_rotation(int len, int chunk) {
 // ---------------------------------------------------------------------------
 template <int NT, int KC, bool HALF, int NA = 1>
 __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W, int j0, int row0, int nrows,
-                                             unsigned char* lds) {
+                                             unsigned char* lds, int rot_seed = -1) {
   static_assert(!HALF || NA == 1, "the half-tile layout has one tile per wavefront");
   const int lane = threadIdx.x & 63;
   const int i = lane & 15, g = lane >> 4;
@@ -303,7 +306,7 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W
   for (int a = 0; a < NA; ++a)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tiles<NA, NT, KC, false, HALF>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC), lds, acc);
+  stream_tiles<NA, NT, KC, false, HALF>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC, rot_seed), lds, acc);
 
   // gate values sit in lanes g < GL, the up values of the same (j, token) GL * 16 lanes higher
   constexpr int GL = HALF ? 1 : 2;
@@ -384,7 +387,7 @@ __global__ __launch_bounds__(256, 4) void ffn_gateup_mfma(FfnArgs p) {
 // ---------------------------------------------------------------------------
 template <int NA, int NT, int KC, bool LO>
 __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, int r0, int kbeg, int kend,
-                                           int slice, int row0, int nrows, unsigned char* lds) {
+                                           int slice, int row0, int nrows, unsigned char* lds, int rot_seed = -1) {
   const int lane = threadIdx.x & 63;
   const int i = lane & 15, g = lane >> 4;
   const int dh = p.dh, dm = p.dm;
@@ -407,7 +410,7 @@ __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, 
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
   stream_tiles<NA, NT, KC, LO>(wx, wy, tok, static_cast<size_t>(p.rows) * dm, kbeg, kend,
-                              start_rotation(kend - kbeg, KC), lds, acc);
+                              start_rotation(kend - kbeg, KC, rot_seed), lds, acc);
   if (!live) return;
   float* y = p.y + static_cast<size_t>(slice) * p.rows * dh;
 #pragma unroll
@@ -504,7 +507,7 @@ constexpr int kWideGateUpJ = 16;  // intermediate indices per wavefront: two til
 constexpr int kWideDownRows = 32; // output rows per wavefront: two tiles
 
 // k chunk per number of token tiles: the staged chunk must give each of the 256 threads a piece
-constexpr int wide_chunk(int nt) { return nt == 1 ? 256 : (nt == 2 ? 128 : 64); }
+constexpr int wide_chunk(int nt) { return nt == 1 ? 256 : 128; }
 
 template <int NA, bool GATEUP, typename Fn>
 __device__ __forceinline__ void wide_rows(int cnt, Fn&& pass) {
@@ -521,36 +524,55 @@ __device__ __forceinline__ void wide_rows(int cnt, Fn&& pass) {
   }
 }
 
+// The hardware hands workgroups to the chip's 8 XCDs round-robin by linear workgroup id, and each
+// XCD has an L2 of its own.  With the parts of a work item numbered along that id, the item's token
+// rows (512 KB for 128 rows of d_h = 2048) are fetched into all eight L2s, and a batch of thousands
+// of tokens does not fit any of them: measured at T = 2048, the gate/up kernel then moves twice the
+// weights' bytes across the fabric.  This renumbering gives every XCD a contiguous range of the
+// `total` working (item, part) pairs, so the parts of an item meet in one L2.  Ids >= total idle.
+constexpr unsigned kXcds = 8;
+__device__ __forceinline__ BlockMap map_block_per_xcd(unsigned items, unsigned parts, bool* idle) {
+  const unsigned id = blockIdx.y * gridDim.x + blockIdx.x, total = items * parts;
+  *idle = id >= total;
+  const unsigned x = id % kXcds, q = total / kXcds, r = total % kXcds;
+  const unsigned v = x * q + min(x, r) + id / kXcds;
+  return BlockMap{static_cast<int>(v / parts), static_cast<int>(v % parts)};
+}
+
 // grid (dm / 64, max items), 256 threads
 __global__ __launch_bounds__(256, 2) void ffn_gateup_mfma_wide(FfnArgs p) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
-  const int w = blockIdx.y;
-  if (w >= *p.n_work) return;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWideLdsBytes];
+  bool idle;
+  const BlockMap at = map_block_per_xcd(*p.n_work, gridDim.x, &idle);
+  if (idle) return;
+  const int w = at.item;
   const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
   const uint16_t* W = static_cast<const uint16_t*>(
       expert_base<SERE_BF16>(p.w_gate_up, p.shared_gate_up, e, p.M, static_cast<size_t>(2) * p.dm * p.dh));
-  const int j0 = (blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kWideGateUpJ;
+  const int j0 = (at.part * kWavesPerBlock + (threadIdx.x >> 6)) * kWideGateUpJ;
   wide_rows<2, true>(cnt, [&](auto nt, int q, int n) {
     constexpr int NT = decltype(nt)::value;
-    gateup_group<NT, wide_chunk(NT), false, 2>(p, W, j0, off + q, n, lds);
+    gateup_group<NT, wide_chunk(NT), false, 2>(p, W, j0, off + q, n, lds, at.part);
   });
 }
 
 // grid (ceil(dh / 128) * ksplit, max items), 256 threads
 __global__ __launch_bounds__(256, 2) void ffn_down_mfma_wide(FfnArgs p) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[kStageLdsBytes];
-  const int w = blockIdx.y;
-  if (w >= *p.n_work) return;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[kWideLdsBytes];
+  bool idle;
+  const BlockMap at = map_block_per_xcd(*p.n_work, gridDim.x, &idle);
+  if (idle) return;
+  const int w = at.item;
   const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
   const uint16_t* W = static_cast<const uint16_t*>(
       expert_base<SERE_BF16>(p.w_down, p.shared_down, e, p.M, static_cast<size_t>(p.dh) * p.dm));
-  const int slab = blockIdx.x / p.ksplit, slice = blockIdx.x % p.ksplit;
+  const int slab = at.part / p.ksplit, slice = at.part % p.ksplit;
   const int r0 = (slab * kWavesPerBlock + (threadIdx.x >> 6)) * kWideDownRows;
   const int blocks = p.dm >> 6, per = (blocks + p.ksplit - 1) / p.ksplit;
   const int kbeg = min(slice * per, blocks) << 6, kend = min((slice + 1) * per, blocks) << 6;
   wide_rows<2, false>(cnt, [&](auto nt, int q, int n) {
     constexpr int NT = decltype(nt)::value;
-    down_group<2, NT, wide_chunk(NT), false>(p, W, r0, kbeg, kend, slice, off + q, n, lds);
+    down_group<2, NT, wide_chunk(NT), false>(p, W, r0, kbeg, kend, slice, off + q, n, lds, at.part);
   });
 }
 

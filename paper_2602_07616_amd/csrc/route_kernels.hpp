@@ -579,10 +579,17 @@ __device__ __forceinline__ void route_phase(const RouteArgs& p, RouteShared& s, 
     p.count_after[tid] = my_cnt;
     p.primary_mask[tid] = s.prim[tid];
     const int first = inc_items - my_items;
+    // Items of 128 rows (prefill-sized batches): an expert with a few rows more than one item
+    // holds is cut into items of about equal size (multiples of a 16-row tile) instead of a full
+    // one and a remnant: its items then take about equally long, and as they are numbered next
+    // to each other they stream the expert's weights side by side, the later one from cache.
+    int per = item_rows;
+    if (item_rows >= 4 * kItemRows && my_items >= 2 && my_items <= 4)
+      per = ((my_cnt + my_items - 1) / my_items + 15) & ~15;
     for (int j = 0; j < my_items; ++j) {
       p.work_expert[first + j] = tid;
-      p.work_off[first + j] = off + j * item_rows;
-      p.work_cnt[first + j] = min(item_rows, my_cnt - j * item_rows);
+      p.work_off[first + j] = off + j * per;
+      p.work_cnt[first + j] = min(per, my_cnt - j * per);
     }
   }
   const int sh_items = (p.T + item_rows - 1) / item_rows;  // per shared expert
