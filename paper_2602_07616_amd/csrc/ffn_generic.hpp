@@ -42,7 +42,15 @@ constexpr int kGenTok = 8;   // tokens served per pass over a weight row
 constexpr int kGenJB = 16;   // intermediate indices per block (gate/up)
 constexpr int kGenRB = 16;   // output rows per block (down)
 
-// h[row, j] = silu(<Wg_j, x>) * <Wu_j, x>.  grid (ceil(dm/kGenJB), M + n_sh), 256 threads.
+constexpr int kGenPerWave = kGenJB / 4;  // weight rows a wavefront serves at a time (gate/up: pairs of rows)
+static_assert(kGenJB == kGenRB && kGenJB % 4 == 0, "four wavefronts share a block's rows evenly");
+
+// h[row, j] = silu(<Wg_j, x>) * <Wu_j, x>.  grid (ceil(dm/kGenJB), max items), 256 threads.
+// A wavefront serves kGenPerWave intermediate indices and kGenTok token rows per pass; all loads
+// of a pass are issued together and unconditionally (token slots beyond the item's rows repeat
+// its first row and are never stored, indices beyond d_m repeat the last one): a load under a
+// condition is waited for on its own, and on a layer this small the kernel is nothing but
+// load latencies.
 template <int DT>
 __global__ __launch_bounds__(256) void ffn_gateup_generic(FfnArgs p) {
   const int w = blockIdx.y;
@@ -51,46 +59,50 @@ __global__ __launch_bounds__(256) void ffn_gateup_generic(FfnArgs p) {
   const int dh = p.dh, dm = p.dm;
   const void* W = expert_base<DT>(p.w_gate_up, p.shared_gate_up, e, p.M, static_cast<size_t>(2) * dm * dh);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int jj = wave; jj < kGenJB; jj += 4) {
-    const int j = blockIdx.x * kGenJB + jj;
-    if (j >= dm) break;
-    for (int tc = 0; tc < cnt; tc += kGenTok) {
-      const int nt = min(kGenTok, cnt - tc);
-      int tok[kGenTok];
+  const int j0 = blockIdx.x * kGenJB + wave * kGenPerWave;
+  if (j0 >= dm) return;
+  for (int tc = 0; tc < cnt; tc += kGenTok) {
+    const int nt = min(kGenTok, cnt - tc);
+    int tok[kGenTok];
 #pragma unroll
-      for (int q = 0; q < kGenTok; ++q) tok[q] = q < nt ? p.sorted_token[off + tc + q] : 0;
-      float ag[kGenTok], au[kGenTok];
+    for (int q = 0; q < kGenTok; ++q) tok[q] = p.sorted_token[off + tc + (q < nt ? q : 0)];
+    float ag[kGenPerWave][kGenTok], au[kGenPerWave][kGenTok];
 #pragma unroll
-      for (int q = 0; q < kGenTok; ++q) ag[q] = au[q] = 0.0f;
-      for (int i = lane * 8; i < dh; i += 512) {
-        float wg[8], wu[8];
-        load8<DT>(W, static_cast<size_t>(j) * dh + i, wg);
-        load8<DT>(W, static_cast<size_t>(dm + j) * dh + i, wu);
+    for (int jj = 0; jj < kGenPerWave; ++jj)
 #pragma unroll
-        for (int q = 0; q < kGenTok; ++q) {
-          if (q < nt) {
-            float xv[8];
-            load8<DT>(p.hidden, static_cast<size_t>(tok[q]) * dh + i, xv);
+      for (int q = 0; q < kGenTok; ++q) ag[jj][q] = au[jj][q] = 0.0f;
+    for (int i = lane * 8; i < dh; i += 512) {
+      float xv[kGenTok][8], wg[kGenPerWave][8], wu[kGenPerWave][8];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-              ag[q] = fmaf(wg[c], xv[c], ag[q]);
-              au[q] = fmaf(wu[c], xv[c], au[q]);
-            }
-          }
-        }
+      for (int jj = 0; jj < kGenPerWave; ++jj) {
+        const int j = min(j0 + jj, dm - 1);
+        load8<DT>(W, static_cast<size_t>(j) * dh + i, wg[jj]);
+        load8<DT>(W, static_cast<size_t>(dm + j) * dh + i, wu[jj]);
       }
+#pragma unroll
+      for (int q = 0; q < kGenTok; ++q) load8<DT>(p.hidden, static_cast<size_t>(tok[q]) * dh + i, xv[q]);
+#pragma unroll
+      for (int jj = 0; jj < kGenPerWave; ++jj)
+#pragma unroll
+        for (int q = 0; q < kGenTok; ++q)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            ag[jj][q] = fmaf(wg[jj][c], xv[q][c], ag[jj][q]);
+            au[jj][q] = fmaf(wu[jj][c], xv[q][c], au[jj][q]);
+          }
+    }
+#pragma unroll
+    for (int jj = 0; jj < kGenPerWave; ++jj)
 #pragma unroll
       for (int q = 0; q < kGenTok; ++q) {
-        if (q < nt) {
-          const float g = wave_sum(ag[q]), u = wave_sum(au[q]);
-          if (lane == 0) p.h[static_cast<size_t>(off + tc + q) * dm + j] = silu(g) * u;
-        }
+        const float g = wave_sum(ag[jj][q]), u = wave_sum(au[jj][q]);
+        if (lane == 0 && q < nt && j0 + jj < dm) p.h[static_cast<size_t>(off + tc + q) * dm + j0 + jj] = silu(g) * u;
       }
-    }
   }
 }
 
-// y[row, r] = <Wd_r, h[row]>.  grid (ceil(dh/kGenRB), M + n_sh), 256 threads.
+// y[row, r] = <Wd_r, h[row]>.  grid (ceil(dh/kGenRB), max items), 256 threads; built like the
+// gate/up kernel.
 template <int DT>
 __global__ __launch_bounds__(256) void ffn_down_generic(FfnArgs p) {
   const int w = blockIdx.y;
@@ -99,35 +111,37 @@ __global__ __launch_bounds__(256) void ffn_down_generic(FfnArgs p) {
   const int dh = p.dh, dm = p.dm;
   const void* W = expert_base<DT>(p.w_down, p.shared_down, e, p.M, static_cast<size_t>(dh) * dm);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int rr = wave; rr < kGenRB; rr += 4) {
-    const int r = blockIdx.x * kGenRB + rr;
-    if (r >= dh) break;
-    for (int tc = 0; tc < cnt; tc += kGenTok) {
-      const int nt = min(kGenTok, cnt - tc);
-      float acc[kGenTok];
+  const int r0 = blockIdx.x * kGenRB + wave * kGenPerWave;
+  if (r0 >= dh) return;
+  for (int tc = 0; tc < cnt; tc += kGenTok) {
+    const int nt = min(kGenTok, cnt - tc);
+    float acc[kGenPerWave][kGenTok];
 #pragma unroll
-      for (int q = 0; q < kGenTok; ++q) acc[q] = 0.0f;
-      for (int j = lane * 8; j < dm; j += 512) {
-        float wd[8];
-        load8<DT>(W, static_cast<size_t>(r) * dm + j, wd);
+    for (int rr = 0; rr < kGenPerWave; ++rr)
 #pragma unroll
-        for (int q = 0; q < kGenTok; ++q) {
-          if (q < nt) {
-            float hv[8];
-            load8<SERE_F32>(p.h, static_cast<size_t>(off + tc + q) * dm + j, hv);
+      for (int q = 0; q < kGenTok; ++q) acc[rr][q] = 0.0f;
+    for (int j = lane * 8; j < dm; j += 512) {
+      float hv[kGenTok][8], wd[kGenPerWave][8];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) acc[q] = fmaf(wd[c], hv[c], acc[q]);
-          }
-        }
-      }
+      for (int rr = 0; rr < kGenPerWave; ++rr)
+        load8<DT>(W, static_cast<size_t>(min(r0 + rr, dh - 1)) * dm + j, wd[rr]);
+#pragma unroll
+      for (int q = 0; q < kGenTok; ++q)
+        load8<SERE_F32>(p.h, static_cast<size_t>(off + tc + (q < nt ? q : 0)) * dm + j, hv[q]);
+#pragma unroll
+      for (int rr = 0; rr < kGenPerWave; ++rr)
+#pragma unroll
+        for (int q = 0; q < kGenTok; ++q)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[rr][q] = fmaf(wd[rr][c], hv[q][c], acc[rr][q]);
+    }
+#pragma unroll
+    for (int rr = 0; rr < kGenPerWave; ++rr)
 #pragma unroll
       for (int q = 0; q < kGenTok; ++q) {
-        if (q < nt) {
-          const float v = wave_sum(acc[q]);
-          if (lane == 0) p.y[static_cast<size_t>(off + tc + q) * dh + r] = v;
-        }
+        const float v = wave_sum(acc[rr][q]);
+        if (lane == 0 && q < nt && r0 + rr < dh) p.y[static_cast<size_t>(off + tc + q) * dh + r0 + rr] = v;
       }
-    }
   }
 }
 

@@ -808,7 +808,7 @@ def test_similarity_feeds_routing(dev):
 
 
 # ------------------------------------------- the launch shape bench.py times ---
-@pytest.mark.parametrize("name", ["qwen3_b32", "qwen3_b128"])
+@pytest.mark.parametrize("name", ["qwen3_b32", "qwen3_b128", "qwen15_b32"])
 def test_graph_replay_matches_eager_and_oracle(dev, name):
     """bench.py replays a HIP graph that holds one decode step per weight copy.
     Capture two steps (two copies of the Qwen3-shaped layer) into a graph, replay
