@@ -138,14 +138,15 @@ struct TokenSource {
 //   lo_plane     : with LO, a second token operand `lo_plane` elements after the
 //                  first is multiplied too (token = high + low bf16 parts)
 // All 256 threads of the workgroup must call this together (it has barriers).
-template <int NA, int NT, int KC, bool LO, bool HALF = false>
+// LDS_BYTES: size of the caller's LDS array (the staging configuration must fit it)
+template <int NA, int NT, int KC, bool LO, bool HALF = false, int LDS_BYTES = kStageLdsBytes>
 __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], const uint16_t* const (&wy)[NA],
                                              const TokenSource& tok, size_t lo_plane, int kbeg, int kend, int rot,
                                              unsigned char* lds, f32x4 (&acc)[NA][NT]) {
   using St = Stage<NT, KC>;
   constexpr int KB = KC / 64;          // 64-wide k blocks per chunk
   constexpr int NP = LO ? 2 : 1;
-  static_assert(NP * 2 * St::kBufBytes <= kWideLdsBytes, "LDS budget");
+  static_assert(NP * 2 * St::kBufBytes <= LDS_BYTES, "LDS budget");
   const int tid = threadIdx.x, lane = tid & 63;
   const int i = lane & 15, g = lane >> 4;
   const int len = kend - kbeg;
@@ -282,7 +283,7 @@ __device__ __forceinline__ int start_rotation(int len, int chunk, int seed = -1)
 // h = silu(gate) * up is stored as bf16 (plus, if split_h, the bf16 rounding
 // residual in a second plane).
 // ---------------------------------------------------------------------------
-template <int NT, int KC, bool HALF, int NA = 1>
+template <int NT, int KC, bool HALF, int NA = 1, int LDS_BYTES = kStageLdsBytes>
 __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W, int j0, int row0, int nrows,
                                              unsigned char* lds, int rot_seed = -1) {
   static_assert(!HALF || NA == 1, "the half-tile layout has one tile per wavefront");
@@ -306,7 +307,7 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W
   for (int a = 0; a < NA; ++a)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tiles<NA, NT, KC, false, HALF>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC, rot_seed), lds, acc);
+  stream_tiles<NA, NT, KC, false, HALF, LDS_BYTES>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC, rot_seed), lds, acc);
 
   // gate values sit in lanes g < GL, the up values of the same (j, token) GL * 16 lanes higher
   constexpr int GL = HALF ? 1 : 2;
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(256, 4) void ffn_gateup_mfma(FfnArgs p) {
 // operand is h_hi + h_lo (two MFMAs per weight fragment).  Partial results go
 // to y[slice][row][r] (fp32).
 // ---------------------------------------------------------------------------
-template <int NA, int NT, int KC, bool LO>
+template <int NA, int NT, int KC, bool LO, int LDS_BYTES = kStageLdsBytes>
 __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, int r0, int kbeg, int kend,
                                            int slice, int row0, int nrows, unsigned char* lds, int rot_seed = -1) {
   const int lane = threadIdx.x & 63;
@@ -409,7 +410,7 @@ __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, 
   for (int a = 0; a < NA; ++a)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tiles<NA, NT, KC, LO>(wx, wy, tok, static_cast<size_t>(p.rows) * dm, kbeg, kend,
+  stream_tiles<NA, NT, KC, LO, false, LDS_BYTES>(wx, wy, tok, static_cast<size_t>(p.rows) * dm, kbeg, kend,
                               start_rotation(kend - kbeg, KC, rot_seed), lds, acc);
   if (!live) return;
   float* y = p.y + static_cast<size_t>(slice) * p.rows * dh;
@@ -552,7 +553,7 @@ __global__ __launch_bounds__(256, 2) void ffn_gateup_mfma_wide(FfnArgs p) {
   const int j0 = (at.part * kWavesPerBlock + (threadIdx.x >> 6)) * kWideGateUpJ;
   wide_rows<2, true>(cnt, [&](auto nt, int q, int n) {
     constexpr int NT = decltype(nt)::value;
-    gateup_group<NT, wide_chunk(NT), false, 2>(p, W, j0, off + q, n, lds, at.part);
+    gateup_group<NT, wide_chunk(NT), false, 2, kWideLdsBytes>(p, W, j0, off + q, n, lds, at.part);
   });
 }
 
@@ -572,7 +573,7 @@ __global__ __launch_bounds__(256, 2) void ffn_down_mfma_wide(FfnArgs p) {
   const int kbeg = min(slice * per, blocks) << 6, kend = min((slice + 1) * per, blocks) << 6;
   wide_rows<2, false>(cnt, [&](auto nt, int q, int n) {
     constexpr int NT = decltype(nt)::value;
-    down_group<2, NT, wide_chunk(NT), false>(p, W, r0, kbeg, kend, slice, off + q, n, lds, at.part);
+    down_group<2, NT, wide_chunk(NT), false, kWideLdsBytes>(p, W, r0, kbeg, kend, slice, off + q, n, lds, at.part);
   });
 }
 
