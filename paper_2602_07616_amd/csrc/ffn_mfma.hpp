@@ -104,19 +104,21 @@ constexpr int kWavesPerBlock = 4;
 // of a 128-bit read fall into 16 different bank groups.
 
 // geometry of one staging configuration
-template <int NT, int KC>
+template <int NT, int KC, int BT = 256>
 struct Stage {
   static constexpr int kRows = NT * kTile;           // token rows held
   static constexpr int kRowBytes = KC * 2 + 16;      // padded LDS row
   static constexpr int kBufBytes = kRows * kRowBytes;
   static constexpr int kPiecesPerRow = KC / 8;       // 16-byte pieces
-  static constexpr int kPerThread = kRows * kPiecesPerRow / 256;
-  static_assert(kPerThread >= 1 && kRows * kPiecesPerRow % 256 == 0, "chunk must split over 256 threads");
+  static constexpr int kPerThread = kRows * kPiecesPerRow / BT;
+  static_assert(kPerThread >= 1 && kRows * kPiecesPerRow % BT == 0, "chunk must split over the workgroup's threads");
 };
 // the largest configuration (eight token tiles, 64-wide chunks), two buffers
 constexpr int kStageLdsBytes = 2 * Stage<8, 64>::kBufBytes;
-// the kernels for prefill-sized batches stage 128-wide chunks of up to eight token tiles
-constexpr int kWideLdsBytes = 2 * Stage<8, 128>::kBufBytes;
+// the kernels for prefill-sized batches stage 128-wide chunks of up to eight token tiles, or
+// 64-wide chunks of sixteen
+constexpr int kWideLdsBytes = 2 * Stage<16, 64>::kBufBytes;
+static_assert(kWideLdsBytes >= 2 * Stage<8, 128>::kBufBytes, "LDS budget");
 static_assert(Stage<8, 64>::kBufBytes >= Stage<4, 128>::kBufBytes && Stage<8, 64>::kBufBytes >= Stage<2, 256>::kBufBytes,
               "LDS budget");
 
@@ -137,13 +139,14 @@ struct TokenSource {
 //                  inside their rows (and thus the same HBM channels)
 //   lo_plane     : with LO, a second token operand `lo_plane` elements after the
 //                  first is multiplied too (token = high + low bf16 parts)
-// All 256 threads of the workgroup must call this together (it has barriers).
+// All BT threads of the workgroup must call this together (it has barriers).
 // LDS_BYTES: size of the caller's LDS array (the staging configuration must fit it)
-template <int NA, int NT, int KC, bool LO, bool HALF = false, int LDS_BYTES = kStageLdsBytes>
+// BT       : threads of the workgroup (all of them stage, every wavefront multiplies every staged tile)
+template <int NA, int NT, int KC, bool LO, bool HALF = false, int LDS_BYTES = kStageLdsBytes, int BT = 256>
 __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], const uint16_t* const (&wy)[NA],
                                              const TokenSource& tok, size_t lo_plane, int kbeg, int kend, int rot,
                                              unsigned char* lds, f32x4 (&acc)[NA][NT]) {
-  using St = Stage<NT, KC>;
+  using St = Stage<NT, KC, BT>;
   constexpr int KB = KC / 64;          // 64-wide k blocks per chunk
   constexpr int NP = LO ? 2 : 1;
   static_assert(NP * 2 * St::kBufBytes <= LDS_BYTES, "LDS budget");
@@ -159,7 +162,7 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
   // re-read the last valid ones; what they deliver is finite and never used): with loads
   // under branches the compiler can no longer count outstanding loads and waits for ALL of
   // them before every use, which would serialise the prefetch.
-  constexpr int kThreadsPerRow = 256 / St::kRows;
+  constexpr int kThreadsPerRow = BT / St::kRows;
   static_assert(St::kPiecesPerRow % kThreadsPerRow == 0 && St::kPiecesPerRow / kThreadsPerRow == St::kPerThread,
                 "a row's pieces must split evenly over its threads");
   const int srow = tid / kThreadsPerRow;
@@ -201,30 +204,43 @@ __device__ __forceinline__ void stream_tiles(const uint16_t* const (&wx)[NA], co
       if (!HALF) ry[a][b] = load_weight(wy[a] + kk);
     }
   };
+  // token tiles whose operands are held at a time: all of them, or four when there are sixteen
+  // (the accumulators alone are then 128 registers)
+  constexpr int TG = NT > 8 ? 4 : NT;
+  static_assert(NT % TG == 0, "token tiles are multiplied in equal groups");
+  // (Issuing a slot's next load as soon as its weights have been merged into the MFMA operands,
+  // i.e. before the block's MFMAs instead of after them, was measured slower: 1-2 % on the decode
+  // layers, 5 % at 1024 tokens.)
   auto multiply_block = [&](int k0, int b, int buf) {
     if (k0 + 64 * b < kend) {  // wave-uniform; a block beyond kend holds a duplicate of the last one
-      u32x4 b_even[NP][NT], b_odd[NP][NT];
-#pragma unroll
-      for (int pl = 0; pl < NP; ++pl)
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const unsigned char* at =
-              lds + (buf * NP + pl) * St::kBufBytes + (t * kTile + i) * St::kRowBytes + (64 * b + 16 * g) * 2;
-          b_even[pl][t] = *reinterpret_cast<const u32x4*>(at);
-          b_odd[pl][t] = *reinterpret_cast<const u32x4*>(at + 16);
-        }
+      u32x4 a_even[NA], a_odd[NA];
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
         // HALF: the tile's rows 8-15 are not used; they multiply whatever the lanes hold
-        const u32x4 a_even = HALF ? rx[a][b] : upper_from(rx[a][b], ry[a][b]);
-        const u32x4 a_odd = HALF ? rotate8(rx[a][b]) : lower_from(ry[a][b], rx[a][b]);
+        a_even[a] = HALF ? rx[a][b] : upper_from(rx[a][b], ry[a][b]);
+        a_odd[a] = HALF ? rotate8(rx[a][b]) : lower_from(ry[a][b], rx[a][b]);
+      }
+#pragma unroll
+      for (int t0 = 0; t0 < NT; t0 += TG) {
+        u32x4 b_even[NP][TG], b_odd[NP][TG];
 #pragma unroll
         for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            acc[a][t] = mfma_bf16(a_even, b_even[pl][t], acc[a][t]);
-            acc[a][t] = mfma_bf16(a_odd, b_odd[pl][t], acc[a][t]);
+          for (int t = 0; t < TG; ++t) {
+            const unsigned char* src = lds + (buf * NP + pl) * St::kBufBytes + ((t0 + t) * kTile + i) * St::kRowBytes +
+                                       (64 * b + 16 * g) * 2;
+            b_even[pl][t] = *reinterpret_cast<const u32x4*>(src);
+            b_odd[pl][t] = *reinterpret_cast<const u32x4*>(src + 16);
           }
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+          for (int pl = 0; pl < NP; ++pl)
+#pragma unroll
+            for (int t = 0; t < TG; ++t) {
+              acc[a][t0 + t] = mfma_bf16(a_even[a], b_even[pl][t], acc[a][t0 + t]);
+              acc[a][t0 + t] = mfma_bf16(a_odd[a], b_odd[pl][t], acc[a][t0 + t]);
+            }
       }
     }
   };
@@ -283,7 +299,9 @@ __device__ __forceinline__ int start_rotation(int len, int chunk, int seed = -1)
 // h = silu(gate) * up is stored as bf16 (plus, if split_h, the bf16 rounding
 // residual in a second plane).
 // ---------------------------------------------------------------------------
-template <int NT, int KC, bool HALF, int NA = 1, int LDS_BYTES = kStageLdsBytes>
+// j0 >= d_m (a wavefront beyond the last intermediate index of a wide workgroup): the wavefront
+// still takes part in the staging, streams the last rows again and stores nothing.
+template <int NT, int KC, bool HALF, int NA = 1, int LDS_BYTES = kStageLdsBytes, int BT = 256>
 __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W, int j0, int row0, int nrows,
                                              unsigned char* lds, int rot_seed = -1) {
   static_assert(!HALF || NA == 1, "the half-tile layout has one tile per wavefront");
@@ -291,6 +309,8 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W
   const int i = lane & 15, g = lane >> 4;
   const int dh = p.dh, dm = p.dm;
   const int chunk = 2 * g + (i >> 3);
+  const bool live = j0 < dm;
+  if (!live) j0 = dm - 8 * NA;
   // HALF: the one half tile holds gate rows j0..j0+3 (tile rows 0-3) and up rows (tile rows 4-7);
   // otherwise tile a holds gate rows j0 + 8a .. +7 (half tile X) and the matching up rows (Y)
   const uint16_t* wx[NA];
@@ -307,7 +327,8 @@ __device__ __forceinline__ void gateup_group(const FfnArgs& p, const uint16_t* W
   for (int a = 0; a < NA; ++a)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tiles<NA, NT, KC, false, HALF, LDS_BYTES>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC, rot_seed), lds, acc);
+  stream_tiles<NA, NT, KC, false, HALF, LDS_BYTES, BT>(wx, wy, tok, 0, 0, dh, start_rotation(dh, KC, rot_seed), lds, acc);
+  if (!live) return;
 
   // gate values sit in lanes g < GL, the up values of the same (j, token) GL * 16 lanes higher
   constexpr int GL = HALF ? 1 : 2;
@@ -386,7 +407,7 @@ __global__ __launch_bounds__(256, 4) void ffn_gateup_mfma(FfnArgs p) {
 // operand is h_hi + h_lo (two MFMAs per weight fragment).  Partial results go
 // to y[slice][row][r] (fp32).
 // ---------------------------------------------------------------------------
-template <int NA, int NT, int KC, bool LO, int LDS_BYTES = kStageLdsBytes>
+template <int NA, int NT, int KC, bool LO, int LDS_BYTES = kStageLdsBytes, int BT = 256>
 __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, int r0, int kbeg, int kend,
                                            int slice, int row0, int nrows, unsigned char* lds, int rot_seed = -1) {
   const int lane = threadIdx.x & 63;
@@ -410,8 +431,8 @@ __device__ __forceinline__ void down_group(const FfnArgs& p, const uint16_t* W, 
   for (int a = 0; a < NA; ++a)
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[a][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  stream_tiles<NA, NT, KC, LO, false, LDS_BYTES>(wx, wy, tok, static_cast<size_t>(p.rows) * dm, kbeg, kend,
-                              start_rotation(kend - kbeg, KC, rot_seed), lds, acc);
+  stream_tiles<NA, NT, KC, LO, false, LDS_BYTES, BT>(wx, wy, tok, static_cast<size_t>(p.rows) * dm, kbeg, kend,
+                                                     start_rotation(kend - kbeg, KC, rot_seed), lds, acc);
   if (!live) return;
   float* y = p.y + static_cast<size_t>(slice) * p.rows * dh;
 #pragma unroll
@@ -508,11 +529,16 @@ constexpr int kWideGateUpJ = 16;  // intermediate indices per wavefront: two til
 constexpr int kWideDownRows = 32; // output rows per wavefront: two tiles
 
 // k chunk per number of token tiles: the staged chunk must give each of the 256 threads a piece
-constexpr int wide_chunk(int nt) { return nt == 1 ? 256 : 128; }
+constexpr int wide_chunk(int nt) { return nt == 1 ? 256 : (nt <= 8 ? 128 : 64); }
 
 template <int NA, bool GATEUP, typename Fn>
 __device__ __forceinline__ void wide_rows(int cnt, Fn&& pass) {
-  // rows of the item in passes of 128 while more than 64 remain, then one pass of <= 64, <= 32 or <= 16
+  // rows of the item: up to 256 in one pass (more than 128: sixteen token tiles); beyond that, passes
+  // of 128 while more than 64 remain; then one pass of <= 64, <= 32 or <= 16
+  if (cnt > 8 * kTile && cnt <= 16 * kTile) {
+    pass(std::integral_constant<int, 16>{}, 0, cnt);
+    return;
+  }
   int q = 0;
   for (; cnt - q > 4 * kTile; q += 8 * kTile) pass(std::integral_constant<int, 8>{}, q, min(8 * kTile, cnt - q));
   const int rem = cnt - q;
@@ -540,8 +566,18 @@ __device__ __forceinline__ BlockMap map_block_per_xcd(unsigned items, unsigned p
   return BlockMap{static_cast<int>(v / parts), static_cast<int>(v % parts)};
 }
 
-// grid (dm / 64, max items), 256 threads
-__global__ __launch_bounds__(256, 2) void ffn_gateup_mfma_wide(FfnArgs p) {
+// Workgroups of the wide kernels: 8 wavefronts, one workgroup per compute unit.  What bounds these
+// kernels is the bytes a compute unit takes in per flop (weights from HBM plus staged token rows
+// from L2, measured at about 30 GB/s per compute unit whatever the mix), so all eight wavefronts
+// multiply the same staged token tiles, each with two weight tiles of its own: 256 weight rows per
+// staged tile (four wavefronts: 128), and a work item holds up to 256 rows (sixteen token tiles, 128
+// accumulator registers), so that an expert with that many rows streams its weights once.
+constexpr int kWideItemRows = 16 * kTile;
+constexpr int kWideThreads = 512;
+constexpr int kWideWaves = kWideThreads / kWave;
+
+// grid (ceil(dm / 128), max items), 512 threads
+__global__ __launch_bounds__(kWideThreads, 1) void ffn_gateup_mfma_wide(FfnArgs p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWideLdsBytes];
   bool idle;
   const BlockMap at = map_block_per_xcd(*p.n_work, gridDim.x, &idle);
@@ -550,15 +586,15 @@ __global__ __launch_bounds__(256, 2) void ffn_gateup_mfma_wide(FfnArgs p) {
   const int e = p.work_expert[w], off = p.work_off[w], cnt = p.work_cnt[w];
   const uint16_t* W = static_cast<const uint16_t*>(
       expert_base<SERE_BF16>(p.w_gate_up, p.shared_gate_up, e, p.M, static_cast<size_t>(2) * p.dm * p.dh));
-  const int j0 = (at.part * kWavesPerBlock + (threadIdx.x >> 6)) * kWideGateUpJ;
+  const int j0 = (at.part * kWideWaves + (threadIdx.x >> 6)) * kWideGateUpJ;  // may lie beyond d_m
   wide_rows<2, true>(cnt, [&](auto nt, int q, int n) {
     constexpr int NT = decltype(nt)::value;
-    gateup_group<NT, wide_chunk(NT), false, 2, kWideLdsBytes>(p, W, j0, off + q, n, lds, at.part);
+    gateup_group<NT, wide_chunk(NT), false, 2, kWideLdsBytes, kWideThreads>(p, W, j0, off + q, n, lds, at.part);
   });
 }
 
-// grid (ceil(dh / 128) * ksplit, max items), 256 threads
-__global__ __launch_bounds__(256, 2) void ffn_down_mfma_wide(FfnArgs p) {
+// grid (ceil(dh / 256) * ksplit, max items), 512 threads
+__global__ __launch_bounds__(kWideThreads, 1) void ffn_down_mfma_wide(FfnArgs p) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[kWideLdsBytes];
   bool idle;
   const BlockMap at = map_block_per_xcd(*p.n_work, gridDim.x, &idle);
@@ -568,12 +604,13 @@ __global__ __launch_bounds__(256, 2) void ffn_down_mfma_wide(FfnArgs p) {
   const uint16_t* W = static_cast<const uint16_t*>(
       expert_base<SERE_BF16>(p.w_down, p.shared_down, e, p.M, static_cast<size_t>(p.dh) * p.dm));
   const int slab = at.part / p.ksplit, slice = at.part % p.ksplit;
-  const int r0 = (slab * kWavesPerBlock + (threadIdx.x >> 6)) * kWideDownRows;
+  const int r0 = (slab * kWideWaves + (threadIdx.x >> 6)) * kWideDownRows;  // may lie beyond d_h
   const int blocks = p.dm >> 6, per = (blocks + p.ksplit - 1) / p.ksplit;
   const int kbeg = min(slice * per, blocks) << 6, kend = min((slice + 1) * per, blocks) << 6;
   wide_rows<2, false>(cnt, [&](auto nt, int q, int n) {
     constexpr int NT = decltype(nt)::value;
-    down_group<2, NT, wide_chunk(NT), false, kWideLdsBytes>(p, W, r0, kbeg, kend, slice, off + q, n, lds, at.part);
+    down_group<2, NT, wide_chunk(NT), false, kWideLdsBytes, kWideThreads>(p, W, r0, kbeg, kend, slice, off + q, n, lds,
+                                                                           at.part);
   });
 }
 

@@ -230,10 +230,13 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
                        ? kTopkThreadsMulti
                        : kRouteThreads;
   r.fine_items = kFineCutBlocks / (c.inter / (2 * kGateUpJ * kWavesPerBlock));
-  // many rows per expert on average (prefill-sized batches): items of 64 or 128 rows, served in one
-  // pass over the weights each
+  // many rows per expert on average (prefill-sized batches): items of 64, 128 or 256 rows, served in
+  // one pass over the weights each
   const long long slots = static_cast<long long>(c.num_tokens) * c.top_k;
-  r.item_rows = slots >= 48ll * c.num_experts ? 4 * kItemRows : (slots >= 24ll * c.num_experts ? 2 * kItemRows : kItemRows);
+  r.item_rows = slots >= 96ll * c.num_experts   ? kWideItemRows
+                : slots >= 48ll * c.num_experts ? 4 * kItemRows
+                : slots >= 24ll * c.num_experts ? 2 * kItemRows
+                                                : kItemRows;
   p.h = reinterpret_cast<float*>(ws + l.h);
   p.y = reinterpret_cast<float*>(ws + l.y);
   return p;
@@ -321,12 +324,11 @@ static void launch_combine(const sere_config& c, const Layout& l, const Pointers
 static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, int ksplit, const FfnArgs& f,
                                hipStream_t s, bool wide = false) {
   if (dtype == SERE_BF16 && wide) {
-    launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_mfma_wide, dim3(inter / (kWideGateUpJ * kWavesPerBlock), max_work),
-                 dim3(256), f);
+    constexpr int kGateUpPerBlock = kWideGateUpJ * kWideWaves, kDownPerBlock = kWideDownRows * kWideWaves;
+    launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_mfma_wide, dim3((inter + kGateUpPerBlock - 1) / kGateUpPerBlock, max_work),
+                 dim3(kWideThreads), f);
     launch_stage(SERE_STAGE_DOWN, s, ffn_down_mfma_wide,
-                 dim3(((hidden + kWideDownRows * kWavesPerBlock - 1) / (kWideDownRows * kWavesPerBlock)) * ksplit,
-                      max_work),
-                 dim3(256), f);
+                 dim3(((hidden + kDownPerBlock - 1) / kDownPerBlock) * ksplit, max_work), dim3(kWideThreads), f);
     return;
   }
   if (dtype == SERE_F32) {

@@ -209,11 +209,10 @@ def test_batch_sweep_decode(dev, T):
         check_output(got if tokens is None else got[tokens], want, wl.spec.dtype, f"T={T} S={S}")
 
 
-def test_prefill_sized_batch(dev):
-    """T = 1024 tokens of the Qwen3-shaped layer (the prefill regime of the paper's
-    appendix on prefill: nearly every expert is primary, nothing to skip).  Integers
-    for the whole batch, outputs on sampled tokens."""
-    T = 1024
+@pytest.mark.parametrize("T", [1024, 2048])
+def test_prefill_sized_batch(dev, T):
+    """T = 1024 and 2048 tokens of the Qwen3-shaped layer (the prefill regime of the paper's
+    appendix on prefill: nearly every expert is primary, nothing to skip).  Integers for the whole batch, outputs on sampled tokens."""
     wl, layer, sim = device_layer(dev, "qwen3_b128", T)
     for S, rho in ((2, 0.0), (8, 0.0)):
         print(f"prefill-sized T={T} S={S}", flush=True)
@@ -297,6 +296,10 @@ EDGE = [
     (wk.F32, 4, 64, 40, 40, 64, 0, 39, 0.0),       # K == M == 40, S = K - 1
     (wk.BF16, 3, 64, 256, 256, 64, 0, 200, 0.0),   # K == M == 256: the largest top-K
     (wk.F32, 5, 64, 4, 2, 64, 16, 1, 0.0),         # maximum number of shared experts
+    # prefill-sized rows per expert (the 8-wavefront kernels), every token compared:
+    (wk.BF16, 100, 320, 5, 4, 448, 0, 2, 0.3),     # items of <= 128 rows; d_m and d_h end inside a workgroup's rows
+    (wk.BF16, 400, 256, 4, 2, 192, 1, 1, 0.0),     # experts of 129..256 rows cut into two equal items, shared expert 3 x 128 + 16
+    (wk.BF16, 700, 128, 3, 2, 128, 0, 2, 0.0),     # experts of several hundred rows, cut into equal items
 ]
 
 
