@@ -247,6 +247,70 @@ __global__ __launch_bounds__(256) void router_logits_tokens_kernel(
   }
 }
 
+// The same for batches of hundreds of tokens and more, where the logits are a dense contraction
+// ([T x d_h] x [d_h x M]) and the vector ALU (fp64 FMAs plus the conversions around them) bounds
+// the kernels above: the fp64 matrix cores (v_mfma_f64_16x16x4) multiply a tile of 16 tokens x 16
+// experts, fed from registers.  A workgroup owns one tile; its four wavefronts take every fourth
+// 32-wide chunk of d_h each, and their partial tiles are added in a fixed order through LDS.
+// Lane l of a wavefront holds row l % 16 of both operands (a token, an expert) and, of every 32
+// consecutive k, the eight from 8 (l / 16) on: one 128-bit load per operand and chunk feeds eight
+// MFMAs (the order of k inside a sum is free as long as both operands agree).  Every logit is the
+// same sequence of operations on its two rows, so bit-identical router rows still give
+// bit-identical logits.  The result tile has lane l hold D[l / 16 + 4 r][l % 16], r = 0..3: with
+// the tokens as rows, a 16-lane row of register r holds one token's 16 logits, which is what the
+// ranking wants.  grid (ceil(M/16), ceil(T/16)), 256 threads.
+typedef double route_f64x4 __attribute__((ext_vector_type(4)));
+template <int DT>
+__global__ __launch_bounds__(256) void router_logits_mfma_kernel(
+    const void* __restrict__ hidden, const void* __restrict__ router_w, uint64_t* __restrict__ list_key,
+    uint8_t* __restrict__ list_id, int T, int M, int dh, int32_t* clear_word) {
+  __shared__ double s_part[4][4][kWave];  // [wavefront][register r][lane]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r16 = lane & 15, kq = lane >> 4;
+  if (clear_word != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *clear_word = 0;
+  const int t0 = blockIdx.y * 16, e0 = blockIdx.x * 16;
+  // rows beyond T or M repeat the last one; their results are not stored
+  const size_t xrow = static_cast<size_t>(min(t0 + r16, T - 1)) * dh + 8 * kq;
+  const size_t wrow = static_cast<size_t>(min(e0 + r16, M - 1)) * dh + 8 * kq;
+  route_f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+  const int nch = dh >> 5;  // 32-wide chunks; this wavefront takes chunks wave, wave + 4, ...
+  constexpr int kAhead = 4; // chunks whose loads are issued together
+  for (int c0 = wave; c0 < nch; c0 += 4 * kAhead) {
+    Raw8<DT> xr[kAhead], wr[kAhead];
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const int c = min(c0 + 4 * u, nch - 1);  // a chunk beyond the row re-reads its end and is not used
+      xr[u].load(hidden, xrow + 32 * static_cast<size_t>(c));
+      wr[u].load(router_w, wrow + 32 * static_cast<size_t>(c));
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      if (c0 + 4 * u < nch) {  // wave-uniform
+        float xv[8], wv[8];
+        xr[u].widen(xv);
+        wr[u].widen(wv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(xv[j]), static_cast<double>(wv[j]), acc, 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) s_part[wave][r][lane] = acc[r];
+  __syncthreads();
+  // wavefront w finishes register w: tokens t0 + kq + 4 w, one per 16-lane row
+  const double logit = ((s_part[0][wave][lane] + s_part[1][wave][lane]) + s_part[2][wave][lane]) + s_part[3][wave][lane];
+  const int t = t0 + kq + 4 * wave, e = e0 + r16;
+  const uint64_t key = e < M ? sortable_key(logit) : 0ull;
+  uint32_t rank = 0;
+  rank_step<1>(key, static_cast<uint32_t>(e), rank);
+  if (t < T) {
+    const size_t at = (static_cast<size_t>(t) * gridDim.x + blockIdx.x) * 16 + rank;
+    list_key[at] = key;
+    list_id[at] = static_cast<uint8_t>(e);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Ordered top-K and gate by merging the sorted lists.  LP (4, 8 or 16) adjacent
 // lanes own one token, lane l of the group holds list l (all 16 entries, in

@@ -244,7 +244,7 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
 
 static int hip_status() { return hipGetLastError() == hipSuccess ? SERE_OK : SERE_ERR_HIP; }
 
-constexpr int kRouterTokensPerBlock = 4;  // batches of >= 256 tokens: a router row serves 4 tokens per fetch
+constexpr int kRouterMfmaTokens = 256;   // batches from this size on: router logits on the fp64 matrix cores
 
 static int launch_router(const sere_config& c, const Pointers& p, const void* hidden,
                          const void* router_w, hipStream_t s) {
@@ -260,7 +260,16 @@ static int launch_router(const sere_config& c, const Pointers& p, const void* hi
                    router_w, p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);           \
     return hip_status();                                                                                        \
   } while (0)
-  if (c.num_tokens >= 256) SERE_LAUNCH_ROUTER_TOKENS(kRouterTokensPerBlock);
+  if (c.num_tokens >= kRouterMfmaTokens) {  // a dense contraction: the fp64 matrix cores
+    const dim3 grid(lists, (c.num_tokens + 15) / 16);
+    if (c.dtype == SERE_F32)
+      launch_stage(SERE_STAGE_ROUTER, s, router_logits_mfma_kernel<SERE_F32>, grid, dim3(256), hidden, router_w,
+                   p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
+    else
+      launch_stage(SERE_STAGE_ROUTER, s, router_logits_mfma_kernel<SERE_BF16>, grid, dim3(256), hidden, router_w,
+                   p.list_key, p.list_id, c.num_tokens, c.num_experts, c.hidden, p.ticket);
+    return hip_status();
+  }
   // fewer tokens: two per fetch, if that still leaves a workgroup for every compute unit
   if (c.num_tokens >= 64 && lists * ((c.num_tokens + 1) / 2) >= 256) SERE_LAUNCH_ROUTER_TOKENS(2);
 #undef SERE_LAUNCH_ROUTER_TOKENS
