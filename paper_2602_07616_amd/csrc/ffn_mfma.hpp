@@ -96,12 +96,20 @@ constexpr int kFineCutBlocks = 2560;  // fine cut while the coarse gate/up grid 
 constexpr int kWavesPerBlock = 4;
 
 // The token operand (hidden states for gate/up, h for down) is shared by the
-// four wavefronts of a workgroup and staged through LDS in k chunks, double
-// buffered: 256 threads copy a chunk of all token rows with 128-bit loads while
+// wavefronts of a workgroup (four; eight in the kernels for prefill-sized
+// batches) and staged through LDS in k chunks, double buffered: all threads of
+// the workgroup copy a chunk of all token rows with 128-bit loads while
 // the previous chunk is being multiplied; lane (g, n) then reads its MFMA
 // operand straight from LDS (row n, k offset 16g: chunk 2g for A_even, 2g+1
-// for A_odd).  A row of the LDS tile is padded by 16 bytes so that the 16 lanes
-// of a 128-bit read fall into 16 different bank groups.
+// for A_odd).  A row of the LDS tile is padded by 16 bytes, which spreads the
+// rows over the banks but does not make these reads conflict-free: measured, a
+// 128-bit LDS read on gfx950 serves lanes {0-3, 12-15, 20-23, 24-27} of each half
+// of the wavefront together and {4-7, 8-11, 16-19, 28-31} together (64 banks), and
+// under that grouping every operand read keeps a two-way conflict whatever the
+// padding.  A layout without conflicts (unpadded rows, 16-byte pieces stored at
+// position p ^ F(row & 15) with a suitable F) was built and verified with the
+// conflict counter, and made no kernel faster: the LDS is not what these
+// kernels wait for.
 
 // geometry of one staging configuration
 template <int NT, int KC, int BT = 256>
@@ -520,15 +528,16 @@ __global__ __launch_bounds__(256, 4) void ffn_down_mfma(FfnArgs p) {
 // blocks with squarer workgroup tiles.  Staging the token tile costs as much
 // traffic from L2 as the weights themselves once the tile holds 128 rows, so a
 // workgroup should cover as many weight rows per staged tile as it can hold
-// accumulators for: two tiles per wavefront and up to eight token tiles per
-// pass, at two workgroups per compute unit (the accumulators alone are 64
-// registers).  The host launches these kernels instead of the ones above when
-// the routing kernel cuts items of 128 rows; bf16 without the split h only.
+// accumulators for: two weight tiles per wavefront and eight (items of up to
+// 128 rows) or sixteen (up to 256 rows) token tiles per pass.  The host launches
+// these kernels instead of the ones above when the routing kernel cuts items
+// of 64 rows or more; bf16 without the split h only.
 // ---------------------------------------------------------------------------
 constexpr int kWideGateUpJ = 16;  // intermediate indices per wavefront: two tiles of 8 gate + 8 up rows
 constexpr int kWideDownRows = 32; // output rows per wavefront: two tiles
 
-// k chunk per number of token tiles: the staged chunk must give each of the 256 threads a piece
+// k chunk per number of token tiles: the staged chunk must give each thread of the workgroup a piece,
+// and two buffers of it must fit the LDS budget
 constexpr int wide_chunk(int nt) { return nt == 1 ? 256 : (nt <= 8 ? 128 : 64); }
 
 template <int NA, bool GATEUP, typename Fn>
