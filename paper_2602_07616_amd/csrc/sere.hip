@@ -244,6 +244,7 @@ static Pointers bind(const sere_config& c, const Layout& l, void* workspace, con
 
 static int hip_status() { return hipGetLastError() == hipSuccess ? SERE_OK : SERE_ERR_HIP; }
 
+constexpr int kGateUpEightWavesRows = 12;  // average rows per expert from which on gate/up workgroups have 8 wavefronts
 constexpr int kRouterMfmaTokens = 256;   // batches from this size on: router logits on the fp64 matrix cores
 
 static int launch_router(const sere_config& c, const Pointers& p, const void* hidden,
@@ -331,7 +332,7 @@ static void launch_combine(const sere_config& c, const Layout& l, const Pointers
 // fp32 layers: vector-ALU kernels.  bf16 layers: matrix-core kernels; `wide`: the variants for
 // batches whose work items hold 128 rows (prefill-sized).
 static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, int ksplit, const FfnArgs& f,
-                               hipStream_t s, bool wide = false) {
+                               hipStream_t s, bool wide = false, bool waves8 = false) {
   if (dtype == SERE_BF16 && wide) {
     constexpr int kGateUpPerBlock = kWideGateUpJ * kWideWaves, kDownPerBlock = kWideDownRows * kWideWaves;
     launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_mfma_wide, dim3((inter + kGateUpPerBlock - 1) / kGateUpPerBlock, max_work),
@@ -346,8 +347,10 @@ static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, i
     launch_stage(SERE_STAGE_DOWN, s, ffn_down_generic<SERE_F32>, dim3((hidden + kGenRB - 1) / kGenRB, max_work),
                  dim3(256), f);
   } else {
-    launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_mfma, dim3(inter / (kGateUpJ * kWavesPerBlock), max_work),
-                 dim3(256), f);
+    if (waves8)
+      launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_mfma<8>, dim3(inter / (kGateUpJ * 8), max_work), dim3(512), f);
+    else
+      launch_stage(SERE_STAGE_GATE_UP, s, ffn_gateup_mfma<4>, dim3(inter / (kGateUpJ * 4), max_work), dim3(256), f);
     launch_stage(SERE_STAGE_DOWN, s, ffn_down_mfma,
                  dim3(((hidden + kDownRows * kWavesPerBlock - 1) / (kDownRows * kWavesPerBlock)) * ksplit, max_work),
                  dim3(256), f);
@@ -357,7 +360,10 @@ static void launch_gateup_down(int dtype, int inter, int hidden, int max_work, i
 static void launch_ffn(const sere_config& c, const Layout& l, const Pointers& p, const FfnArgs& f, void* out,
                        hipStream_t s) {
   const bool wide = c.dtype == SERE_BF16 && !f.split_h && p.route.item_rows >= 2 * kItemRows;
-  launch_gateup_down(c.dtype, c.inter, c.hidden, l.max_work, l.ksplit, f, s, wide);
+  // a dozen rows per expert and more: the gate/up workgroups of eight wavefronts (the routing
+  // kernel's choice of the cut counts workgroups of four; both cuts halve alike)
+  const bool waves8 = static_cast<long long>(c.num_tokens) * c.top_k >= kGateUpEightWavesRows * c.num_experts;
+  launch_gateup_down(c.dtype, c.inter, c.hidden, l.max_work, l.ksplit, f, s, wide, waves8);
   launch_combine(c, l, p, f.hidden, out, s);
 }
 
