@@ -811,7 +811,7 @@ def test_similarity_feeds_routing(dev):
 
 
 # ------------------------------------------- the launch shape bench.py times ---
-@pytest.mark.parametrize("name", ["qwen3_b32", "qwen3_b128", "qwen15_b32"])
+@pytest.mark.parametrize("name", ["qwen3_b32", "qwen3_b128", "qwen15_b32", "dsv2lite_b64", "mixtral_b64"])
 def test_graph_replay_matches_eager_and_oracle(dev, name):
     """bench.py replays a HIP graph that holds one decode step per weight copy.
     Capture two steps (two copies of the Qwen3-shaped layer) into a graph, replay
@@ -824,8 +824,9 @@ def test_graph_replay_matches_eager_and_oracle(dev, name):
     copy = dev.DeviceLayer.from_workload(
         wl, sim, 2, 0.0, weights=tuple(None if t is None else t.clone() for t in layer.weights()))
     layers = [layer, copy]
+    S, rho = wl.spec.grid[0]   # the setting bench.py's headline line uses for this layer
     for l in layers:
-        l.set_knobs(2, 0.0)
+        l.set_knobs(S, rho)
         l.out.zero_()
         l.run_decode(with_outputs=False)
     torch.cuda.synchronize()
@@ -849,7 +850,7 @@ def test_graph_replay_matches_eager_and_oracle(dev, name):
         torch.cuda.synchronize()
         for l, e in zip(layers, eager):
             assert (l.out == e).all(), f"replay {rep}"
-    ref = oracle_route(wl, sim, 2, 0.0, name)
+    ref = oracle_route(wl, sim, S, rho, name)
     tokens = [0, 5, 11, 17, 23, 31]
     want = oracle_output(wl, ref.rerouted_ids, ref.topk_weights, name, tokens)
     check_output(layers[1].out_to_host_f64()[tokens], want, wl.spec.dtype, "graph replay")
